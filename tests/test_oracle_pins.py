@@ -1,0 +1,370 @@
+"""Pins for the CPU oracle (no GPU): the oracle is checked against things other than itself.
+
+* an exhaustive sort written with numpy float32 element-wise ops (a different code path);
+* closed forms on integer lattices and collinear points (fix tie-breaking analytically);
+* hand-worked golden values (tests/golden/knn_tiny_2d.txt);
+* invariants stated by Algorithm 2 of the paper (self at slot 0, never its own candidate,
+  searches inside the row split) and mathematical ones (bitwise symmetry, exact power-of-two
+  scaling, permutation consistency, denormals kept, no fused multiply-add);
+* a float64 KD-tree (scipy) as a loose library cross-check;
+* backward: central finite differences of a float64 loss, translation invariance, Euler's
+  identity for degree-2 homogeneity, a hand-worked lattice case.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2511_10442_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# --------------------------------------------------------------------------- #
+# second code path: exhaustive sort in numpy, fp32 ops individually rounded
+# --------------------------------------------------------------------------- #
+def exhaustive_knn(coords, row_splits, k):
+    coords = np.asarray(coords, dtype=np.float32)
+    n, d = coords.shape
+    idx = np.full((n, k), -1, dtype=np.int32)
+    d2o = np.zeros((n, k), dtype=np.float32)
+    for s in range(len(row_splits) - 1):
+        b, e = int(row_splits[s]), int(row_splits[s + 1])
+        for v in range(b, e):
+            acc = None
+            for c in range(d):
+                delta = (coords[v, c] - coords[b:e, c]).astype(np.float32)
+                sq = (delta * delta).astype(np.float32)
+                acc = sq if acc is None else (acc + sq).astype(np.float32)
+            others = np.array([u for u in range(b, e) if u != v], dtype=np.int64)
+            dd = acc[others - b]
+            order = np.lexsort((others, dd))        # primary d2, secondary index
+            take = order[: k - 1]
+            idx[v, 0] = v
+            idx[v, 1:1 + len(take)] = others[take]
+            d2o[v, 1:1 + len(take)] = dd[take]
+    return idx, d2o
+
+
+def assert_same(a_idx, a_d2, b_idx, b_d2):
+    assert np.array_equal(a_idx, b_idx)
+    assert np.array_equal(a_d2.view(np.uint32), b_d2.view(np.uint32))   # bit-exact, incl. signed zero
+
+
+@pytest.mark.parametrize("d", [1, 2, 3, 4, 5, 8, 10])
+@pytest.mark.parametrize("n,k", [(1, 1), (1, 4), (7, 3), (33, 8), (64, 67), (50, 50)])
+def test_matches_exhaustive_sort(d, n, k):
+    x, rs = W.uniform(n, d, seed=100 * d + n + k)
+    assert_same(*oracle.knn(x, rs, k), *exhaustive_knn(x, rs, k))
+
+
+@pytest.mark.parametrize("d", [2, 3, 5])
+def test_matches_exhaustive_sort_ragged_with_ties(d):
+    sizes = [0, 5, 1, 0, 17, 2, 30, 0]
+    n = sum(sizes)
+    x, rs = W.quantised(n, d, levels=3, seed=7 + d, sizes=sizes)
+    for k in (1, 2, 6, 40):
+        assert_same(*oracle.knn(x, rs, k), *exhaustive_knn(x, rs, k))
+
+
+def test_rows_variant_equals_full():
+    x, rs = W.uniform(500, 3, seed=5, sizes=[200, 0, 300])
+    idx, d2 = oracle.knn(x, rs, 9)
+    rows = np.array([0, 199, 200, 499, 250, 17], dtype=np.int64)
+    ridx, rd2 = oracle.knn_rows(x, rs, 9, rows)
+    assert_same(ridx, rd2, idx[rows], d2[rows])
+
+
+# --------------------------------------------------------------------------- #
+# golden, hand-worked
+# --------------------------------------------------------------------------- #
+def test_golden_tiny_2d():
+    pts, rows = {}, {}
+    for line in open(os.path.join(GOLDEN, "knn_tiny_2d.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        if t[0] == "P":
+            pts[int(t[1])] = (float(t[2]), float(t[3]))
+        elif t[0] == "R":
+            vals = t[2:]
+            rows[int(t[1])] = [(int(vals[2 * j]), float(vals[2 * j + 1])) for j in range(3)]
+    x = np.array([pts[i] for i in range(6)], dtype=np.float32)
+    rs = np.array([0, 4, 6], dtype=np.int32)
+    idx, d2 = oracle.knn(x, rs, 3)
+    for v in range(6):
+        assert [int(i) for i in idx[v]] == [p[0] for p in rows[v]]
+        assert [float(q) for q in d2[v]] == [p[1] for p in rows[v]]
+
+
+# --------------------------------------------------------------------------- #
+# closed forms
+# --------------------------------------------------------------------------- #
+def _shell_counts():
+    out = {}
+    for line in open(os.path.join(GOLDEN, "lattice_shell_counts.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        out[int(t[0])] = [int(v) for v in t[1:]]
+    return out
+
+
+@pytest.mark.parametrize("d,m", [(2, 9), (3, 7)])
+def test_lattice_interior_point(d, m):
+    """Interior lattice point: sorted d2 sequence = representation counts; ties resolved by
+    lower row-major index, computed here with integers only."""
+    x, rs = W.lattice(m, d)
+    centre = tuple([m // 2] * d)
+    strides = [m ** (d - 1 - c) for c in range(d)]
+    v = sum(c * s for c, s in zip(centre, strides))
+    reach = m // 2
+    offs = [o for o in itertools.product(range(-reach, reach + 1), repeat=d) if any(o)]
+    keyed = sorted((sum(c * c for c in o), v + sum(c * s for c, s in zip(o, strides))) for o in offs)
+    # only norms <= reach^2 are guaranteed complete inside the lattice
+    complete = [kv for kv in keyed if kv[0] <= reach * reach]
+    k = len(complete) + 1
+    idx, d2 = oracle.knn(x, rs, k)
+    assert idx[v, 0] == v and d2[v, 0] == 0.0
+    assert [int(i) for i in idx[v, 1:]] == [kv[1] for kv in complete]
+    assert [float(q) for q in d2[v, 1:]] == [float(kv[0]) for kv in complete]
+    counts = _shell_counts()[d]
+    for s in range(1, min(len(counts), reach * reach + 1)):
+        assert int(np.sum(d2[v, 1:] == float(s))) == counts[s]
+
+
+@pytest.mark.parametrize("d", [2, 3, 7])
+def test_collinear_points(d):
+    n, k = 41, 9
+    x, rs = W.collinear(n, d)
+    idx, d2 = oracle.knn(x, rs, k)
+    i = 20
+    expect = [i]
+    for j in range(1, 5):
+        expect += [i - j, i + j]            # equal distance: lower index first
+    assert [int(t) for t in idx[i]] == expect
+    assert [float(t) for t in d2[i]] == [0.0] + [float(j * j) for j in range(1, 5) for _ in (0, 1)]
+    # end point: neighbours only on one side
+    assert [int(t) for t in idx[0]] == list(range(0, k))
+    assert [float(t) for t in d2[0]] == [float(j * j) for j in range(k)]
+
+
+def test_all_duplicates_segment():
+    n, k = 23, 7
+    x = np.full((n, 3), 0.375, dtype=np.float32)
+    idx, d2 = oracle.knn(x, np.array([0, n], dtype=np.int32), k)
+    assert np.all(d2 == 0.0)
+    for v in range(n):
+        others = [u for u in range(n) if u != v][: k - 1]
+        assert [int(t) for t in idx[v]] == [v] + others     # self first even if a duplicate has a lower index
+
+
+def test_short_segment_padding():
+    x, rs = W.uniform(6, 3, seed=3, sizes=[2, 0, 1, 3])
+    idx, d2 = oracle.knn(x, rs, 4)
+    assert [int(t) for t in idx[0]] == [0, 1, -1, -1] and d2[0, 2] == 0.0 and d2[0, 3] == 0.0
+    assert [int(t) for t in idx[2]] == [2, -1, -1, -1] and np.all(d2[2] == 0.0)
+    assert set(int(t) for t in idx[4]) == {3, 4, 5, -1}
+
+
+# --------------------------------------------------------------------------- #
+# invariants
+# --------------------------------------------------------------------------- #
+@pytest.fixture(scope="module")
+def medium():
+    sizes = [700, 0, 1300, 48]
+    x, rs = W.uniform(sum(sizes), 4, seed=11, sizes=sizes)
+    k = 12
+    idx, d2 = oracle.knn(x, rs, k)
+    return x, rs, k, idx, d2
+
+
+def test_self_first_unique_in_segment_sorted(medium):
+    x, rs, k, idx, d2 = medium
+    n = x.shape[0]
+    assert np.array_equal(idx[:, 0], np.arange(n)) and np.all(d2[:, 0] == 0.0)
+    seg = np.searchsorted(rs[1:], np.arange(n), side="right")
+    for v in range(n):
+        row = idx[v]
+        valid = row[row >= 0]
+        assert len(set(valid.tolist())) == len(valid)              # no index twice, self only at slot 0
+        assert np.all(seg[valid] == seg[v])                        # never crosses a row split
+        dd = d2[v, 1:]
+        ii = idx[v, 1:]
+        ok = (dd[:-1] < dd[1:]) | ((dd[:-1] == dd[1:]) & (ii[:-1] < ii[1:]))
+        assert np.all(ok[(ii[:-1] >= 0) & (ii[1:] >= 0)])
+
+
+def test_bitwise_symmetry(medium):
+    x, rs, k, idx, d2 = medium
+    lookup = {}
+    for v in range(x.shape[0]):
+        for j in range(1, k):
+            if idx[v, j] >= 0:
+                lookup[(v, int(idx[v, j]))] = d2[v, j]
+    both = [(a, b) for (a, b) in lookup if (b, a) in lookup]
+    assert len(both) > 1000
+    for a, b in both:
+        assert lookup[(a, b)] == lookup[(b, a)]
+
+
+def test_exact_power_of_two_scaling(medium):
+    x, rs, k, idx, d2 = medium
+    idx2, d22 = oracle.knn(x * np.float32(8.0), rs, k)
+    assert np.array_equal(idx, idx2)
+    assert np.array_equal(d22, d2 * np.float32(64.0))
+
+
+def test_permutation_consistency():
+    x, rs = W.uniform(400, 3, seed=21)
+    k = 10
+    idx, d2 = oracle.knn(x, rs, k)
+    perm = np.random.Generator(np.random.PCG64(5)).permutation(400)
+    idxp, d2p = oracle.knn(x[perm], rs, k)
+    # row i of the permuted problem is old row perm[i]; distances identical; indices map back
+    assert np.array_equal(d2p, d2[perm])
+    assert np.array_equal(perm[idxp], idx[perm])          # no ties in continuous data
+
+
+def test_segment_independence():
+    sizes = [120, 80, 0, 200]
+    x, rs = W.uniform(sum(sizes), 5, seed=31, sizes=sizes)
+    k = 6
+    idx, d2 = oracle.knn(x, rs, k)
+    for s in range(len(sizes)):
+        b, e = int(rs[s]), int(rs[s + 1])
+        if e == b:
+            continue
+        i1, q1 = oracle.knn(x[b:e], np.array([0, e - b], dtype=np.int32), k)
+        i1 = np.where(i1 >= 0, i1 + b, -1)
+        assert_same(i1, q1, idx[b:e], d2[b:e])
+
+
+def test_denormals_kept_and_no_fma():
+    # squares of 1e-20 are ~1e-40: denormal in fp32, must not flush to zero
+    x = np.array([[0, 0], [1e-20, 0], [2e-20, 0], [0, 3e-20]], dtype=np.float32)
+    idx, d2 = oracle.knn(x, np.array([0, 4], dtype=np.int32), 4)
+    assert [int(t) for t in idx[0]] == [0, 1, 2, 3]
+    assert d2[0, 1] > 0 and d2[0, 1] < d2[0, 2] < d2[0, 3]
+    e = np.float32(1e-20) * np.float32(1e-20)
+    assert d2[0, 1] == e
+    # a pair where a fused multiply-add would round differently from mul-then-add
+    rng = np.random.Generator(np.random.PCG64(77))
+    found = 0
+    for _ in range(2000):
+        a, b = rng.random(2).astype(np.float32)
+        sep = np.float32(np.float32(a * a) + np.float32(b * b))
+        fused = np.float32(float(np.float32(a * a)) + float(b) * float(b))   # one rounding for b*b+acc
+        if sep != fused:
+            found += 1
+            xx = np.array([[a, b], [0, 0]], dtype=np.float32)
+            _, q = oracle.knn(xx, np.array([0, 2], dtype=np.int32), 2)
+            assert q[0, 1] == sep
+    assert found > 50
+
+
+def test_loose_check_against_float64_kdtree():
+    from scipy.spatial import cKDTree
+    x, rs = W.uniform(3000, 3, seed=41)
+    k = 8
+    idx, d2 = oracle.knn(x, rs, k)
+    dist, ind = cKDTree(x.astype(np.float64)).query(x.astype(np.float64), k=k)
+    assert np.allclose(d2, dist ** 2, rtol=1e-5, atol=1e-10)
+    assert np.mean(ind == idx) > 0.999
+
+
+def test_kth_distance_scale_uniform():
+    """Uniform density rho in 3-D: the ball holding K points has radius (3K/(4 pi rho))^(1/3)."""
+    w = W.config1()
+    idx, d2 = oracle.knn(w.coords, w.row_splits, w.k)
+    inner = np.all((w.coords > 0.2) & (w.coords < 0.8), axis=1)
+    r_k = np.sqrt(d2[inner, -1]).mean()
+    expect = (3 * (w.k - 1) / (4 * np.pi * w.n)) ** (1 / 3)
+    assert abs(r_k / expect - 1) < 0.05
+
+
+# --------------------------------------------------------------------------- #
+# bins-per-dimension heuristic
+# --------------------------------------------------------------------------- #
+def test_paper_n_bins_golden():
+    for line in open(os.path.join(GOLDEN, "n_bins_paper.txt")):
+        t = line.split()
+        if not t or t[0].startswith("#"):
+            continue
+        n, s, k, d = int(t[0]), int(t[1]), int(t[2]), int(t[3])
+        assert oracle.paper_n_bins(n, s, k, d) == (int(t[5]), int(t[6]))
+
+
+# --------------------------------------------------------------------------- #
+# backward
+# --------------------------------------------------------------------------- #
+def _loss64(xflat, shape, idx, g):
+    x = xflat.reshape(shape)
+    total = 0.0
+    for v in range(shape[0]):
+        for j in range(idx.shape[1]):
+            u = idx[v, j]
+            if u >= 0:
+                total += g[v, j] * np.sum((x[v] - x[u]) ** 2)
+    return total
+
+
+@pytest.mark.parametrize("d", [2, 3, 6])
+def test_backward_finite_differences(d):
+    sizes = [9, 3, 14]
+    n = sum(sizes)
+    x, rs = W.uniform(n, d, seed=51 + d, sizes=sizes)
+    k = 5
+    idx, _ = oracle.knn(x, rs, k)
+    g = W.upstream_grad(n, k, seed=61)
+    grad, _ = oracle.knn_backward(g, idx, x)
+    x64 = x.astype(np.float64).reshape(-1)
+    g64 = g.astype(np.float64)
+    h = 1e-4
+    num = np.zeros_like(x64)
+    for i in range(x64.size):
+        xp, xm = x64.copy(), x64.copy()
+        xp[i] += h
+        xm[i] -= h
+        num[i] = (_loss64(xp, x.shape, idx, g64) - _loss64(xm, x.shape, idx, g64)) / (2 * h)
+    # the loss is quadratic, so central differences are exact up to rounding
+    assert np.allclose(grad.reshape(-1), num, rtol=1e-8, atol=1e-8)
+
+
+def test_backward_translation_invariance_and_euler():
+    sizes = [300, 500]
+    n = sum(sizes)
+    x, rs = W.uniform(n, 4, seed=71, sizes=sizes)
+    k = 10
+    idx, d2 = oracle.knn(x, rs, k)
+    g = W.upstream_grad(n, k, seed=72)
+    grad, asum = oracle.knn_backward(g, idx, x)
+    for s in range(2):
+        b, e = int(rs[s]), int(rs[s + 1])
+        assert np.all(np.abs(grad[b:e].sum(axis=0)) < 1e-9 * asum[b:e].sum(axis=0))
+    # d2 is homogeneous of degree 2 in the coordinates: sum_v x_v . G_v = 2 sum g d2
+    d2_64 = np.zeros((n, k))
+    for j in range(k):
+        d2_64[:, j] = np.sum((x.astype(np.float64) - x[idx[:, j]].astype(np.float64)) ** 2, axis=1)
+    lhs = np.sum(x.astype(np.float64) * grad)
+    rhs = 2.0 * np.sum(g.astype(np.float64) * d2_64)
+    assert abs(lhs - rhs) < 1e-9 * np.sum(np.abs(g) * d2_64)
+    # the float32 distances the forward returned are those distances, to fp32 rounding
+    assert np.allclose(d2, d2_64, rtol=1e-5, atol=0)
+
+
+def test_backward_by_hand_and_padding():
+    # three collinear points 0,1,3 on the first axis; K=2: neighbours 0->1, 1->0, 2->1
+    x = np.array([[0, 0], [1, 0], [3, 0]], dtype=np.float32)
+    idx, d2 = oracle.knn(x, np.array([0, 3], dtype=np.int32), 2)
+    assert idx.tolist() == [[0, 1], [1, 0], [2, 1]] and d2[:, 1].tolist() == [1.0, 1.0, 4.0]
+    g = np.array([[5, 1], [7, 2], [9, 3]], dtype=np.float32)       # slot-0 gradients must not matter
+    grad, _ = oracle.knn_backward(g, idx, x)
+    # L = 1*(x0-x1)^2 + 2*(x1-x0)^2 + 3*(x2-x1)^2 ; dL/dx0 = 2*3*(x0-x1) = -6 ; dL/dx2 = 6*(x2-x1) = 12
+    assert grad[:, 0].tolist() == [-6.0, -6.0, 12.0] and np.all(grad[:, 1] == 0.0)
+    # padded entries carry nothing
+    idx_pad = np.array([[0, -1], [1, -1], [2, -1]], dtype=np.int32)
+    grad, asum = oracle.knn_backward(g, idx_pad, x)
+    assert np.all(grad == 0.0) and np.all(asum == 0.0)
