@@ -1,0 +1,148 @@
+/* fastgraph.h -- C ABI of the MI355X-native binned exact k-nearest-neighbour graph build.
+ *
+ * The operations follow the problem statement of FastGraph (arXiv 2511.10442), Section 3
+ * "Optimized K-Nearest Neighbor Algorithm": points of a ragged batch (row splits) are
+ * partitioned into a regular grid of bins, sorted by bin, and every point searches shells of
+ * neighbouring bins of growing radius until its K best squared distances are certified
+ * against everything unsearched (Algorithm 1, Algorithm 2); gradients of the returned squared
+ * distances flow back to the coordinates (Section 3, last paragraph).
+ *
+ * Conventions for every entry point
+ *   - Every array pointer is a DEVICE pointer unless the comment says "host".
+ *   - The caller owns every buffer.  The library allocates no device memory, keeps no global
+ *     state, never synchronises the stream and never throws.  Inputs are never modified.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; outputs are valid once the stream has reached that point.
+ *   - `workspace` is device memory of at least fg_workspace_size() bytes, 256-byte aligned.
+ *     Its contents are scratch: undefined on entry, undefined after the call except for the
+ *     arrays an fg_binning view points into (valid until the workspace is reused).
+ *   - Every call returns an fg_status; on any status other than FG_OK nothing was enqueued.
+ *   - Preconditions that cannot be checked without a device round trip are documented, not
+ *     checked: row_splits[0] = 0, row_splits[S] = n, non-decreasing; all coordinates finite.
+ *   - n must be below 2^31 (indices are int32).  2 <= d <= 10.  1 <= k <= 128.
+ */
+#ifndef FASTGRAPH_H
+#define FASTGRAPH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FG_OK = 0,
+    FG_ERR_NULL = 1,        /* a required pointer is NULL */
+    FG_ERR_BAD_SHAPE = 2,   /* n < 0, n >= 2^31, n_segments < 1, k < 1, n_bins/d_bin out of range, too many bins */
+    FG_ERR_UNSUPPORTED = 3, /* d outside 2..10, k > 128, d_bin outside 2..5 */
+    FG_ERR_WORKSPACE = 4,   /* workspace too small or not 256-byte aligned */
+    FG_ERR_LAUNCH = 5       /* the HIP runtime reported an error at launch */
+} fg_status;
+
+/* Largest values accepted. */
+#define FG_MAX_D 10
+#define FG_MIN_D 2
+#define FG_MAX_K 128
+#define FG_MIN_D_BIN 2
+#define FG_MAX_D_BIN 5
+#define FG_MAX_TOTAL_BINS (1 << 28) /* n_segments * n_bins^d_bin */
+
+/* Human-readable name of a status (host pointer to a static string). */
+const char* fg_status_string(fg_status status);
+
+/* Bins per dimension and number of binning dimensions (Section 3, the equation
+ *   n_bins = (32 * n_elems / K)^(1/d_max), n_elems = mean points per row split,
+ * "clamped to [5, 30]", and the paragraph limiting binning to the first <= 5 dimensions).
+ *   mode 0: the paper's heuristic as printed: d_bin = min(d, 5), value truncated, clamped to [5,30].
+ *   mode 1: tuned for MI355X: same functional form with this build's own constant, binning
+ *           dimensions and upper clamp (a finer grid; the paper notes the value is hardware
+ *           specific and user-adjustable).
+ * The choice never changes the result of the search, only its speed.
+ * n_bins, d_bin: host out.  Pure host arithmetic; touches no device. */
+fg_status fg_auto_n_bins(int64_t n, int32_t n_segments, int32_t k, int32_t d, int32_t mode,
+                         int32_t* n_bins, int32_t* d_bin);
+
+/* Bytes of workspace needed by fg_bin_points / fg_binned_select_knn / fg_knn_backward for this
+ * problem (n_bins <= 0 or d_bin <= 0: the values fg_auto_n_bins mode 1 would choose).
+ * bytes: host out.  O(n * (d + 4) + n_segments * n_bins^d_bin) words ("virtually no memory
+ * overhead", Abstract). */
+fg_status fg_workspace_size(int64_t n, int32_t d, int32_t n_segments, int32_t k,
+                            int32_t n_bins, int32_t d_bin, size_t* bytes);
+
+/* Result of the binning stage: device pointers into the caller's workspace. */
+typedef struct {
+    const int32_t* bin_idx;    /* [n]  flat bin of each point, ORIGINAL order; segment s owns bins [s*T, (s+1)*T) */
+    const int32_t* perm;       /* [n]  sorted position -> original row index */
+    const int32_t* bin_bounds; /* [n_segments*T + 1] exclusive prefix of bin populations: bin b holds
+                                  sorted positions [bin_bounds[b], bin_bounds[b+1]) */
+    const float* sorted_soa;   /* [d][soa_stride] coordinates in bin order, structure of arrays */
+    const float* seg_geom;     /* [n_segments][d_bin][4]: lower box edge, bins per unit length (0 if the
+                                  segment has zero extent in that dimension), bin width, rounding slack */
+    int64_t soa_stride;        /* elements between consecutive coordinate rows of sorted_soa */
+    int64_t cells_per_segment; /* T = n_bins^d_bin */
+    int32_t n_bins;            /* bins per binning dimension actually used */
+    int32_t d_bin;             /* binning dimensions actually used (the first d_bin coordinates) */
+} fg_binning;
+
+/* Spatial partition + counting sort (Section 3: "points are sorted by bin assignments and
+ * cumulative boundaries are created for each bin"; Algorithm 2 inputs binIdx, binBounds,
+ * binCounts, binWidths; Algorithm 1's row-major flattening with the last dimension fastest).
+ * Per row split: bounding box over the first d_bin coordinates; bin of a point in dimension c =
+ * min(n_bins-1, floor((x_c - lo_c) * n_bins / (hi_c - lo_c))), 0 if hi_c == lo_c.
+ *   coords      [n][d] row-major float32
+ *   row_splits  [n_segments+1] int32
+ *   n_bins      bins per dimension, <= 0: auto (mode 1);  d_bin likewise
+ *   view        host out: where the results live inside `workspace`
+ * The order of points inside one bin is unspecified.  n == 0: FG_OK, nothing enqueued. */
+fg_status fg_bin_points(const float* coords, const int32_t* row_splits, int64_t n, int32_t d,
+                        int32_t n_segments, int32_t k_hint, int32_t n_bins, int32_t d_bin,
+                        void* workspace, size_t workspace_bytes, fg_binning* view, void* stream);
+
+/* Exact K nearest neighbours of every point inside its own row split (Algorithm 2;
+ * fg_bin_points followed by the shell-expanding query kernel).
+ *   out_idx [n][k] int32   slot 0 = the row itself; slots 1.. = the k-1 nearest other points of
+ *                          the row split as ORIGINAL row indices, ascending by (squared distance,
+ *                          index); -1 where the row split has fewer than k points
+ *   out_d2  [n][k] float32 matching squared distances (0 at slot 0 and at padding); each is the
+ *                          left-to-right float32 sum over all d coordinates of the float32 squares
+ *                          of the float32 differences, every operation rounded on its own
+ * Rows are in the caller's original order.  The result is deterministic and independent of
+ * n_bins, d_bin, the stream and the run.  k_hint of fg_bin_points is k here. */
+fg_status fg_binned_select_knn(const float* coords, const int32_t* row_splits, int64_t n,
+                               int32_t d, int32_t n_segments, int32_t k, int32_t n_bins,
+                               int32_t d_bin, int32_t* out_idx, float* out_d2,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same as fg_binned_select_knn, and additionally writes, per row, the number of candidate
+ * squared distances evaluated for it (Algorithm 2's inner loop trip count) into
+ * out_candidates [n] int32 (may not be NULL).  For measurement; slower than the plain call. */
+fg_status fg_binned_select_knn_counted(const float* coords, const int32_t* row_splits, int64_t n,
+                                       int32_t d, int32_t n_segments, int32_t k, int32_t n_bins,
+                                       int32_t d_bin, int32_t* out_idx, float* out_d2,
+                                       int32_t* out_candidates,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Query stage alone on an existing binning (what fg_binned_select_knn runs after
+ * fg_bin_points); `view` must come from fg_bin_points on the same coords/row_splits and its
+ * workspace must still be intact.  Used to time the query kernel on its own. */
+fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int64_t n, int32_t d,
+                          int32_t n_segments, int32_t k, int32_t* out_idx, float* out_d2,
+                          int32_t* out_candidates /* may be NULL */, void* stream);
+
+/* Backward of the squared distances (Section 3, last paragraph):
+ *   grad_coords[v][c]  = sum_j grad_d2[v][j] * 2 * (x[v][c] - x[idx[v][j]][c])
+ *                      - sum_{(w,j): idx[w][j] = v} grad_d2[w][j] * 2 * (x[w][c] - x[v][c])
+ * over entries with idx >= 0.
+ *   grad_d2 [n][k] float32, idx [n][k] int32 (as returned by the forward), coords [n][d]
+ *   grad_coords [n][d] float32, overwritten (zero-filled by the call, then accumulated with
+ *   float32 atomics: the summation order, hence the last bits, may differ between runs).
+ * workspace may be NULL (none is needed). */
+fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float* coords,
+                          int64_t n, int32_t d, int32_t k, float* grad_coords,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTGRAPH_H */

@@ -1,0 +1,248 @@
+"""Thin ctypes binding of libfastgraph_hip.so (same names as include/fastgraph.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels behind the C ABI.
+PyTorch is used for device memory and for the current HIP stream, nothing else.  There is no
+CPU fallback: if the library has not been built this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfastgraph_hip.so")
+
+FG_OK = 0
+FG_ERR_NULL = 1
+FG_ERR_BAD_SHAPE = 2
+FG_ERR_UNSUPPORTED = 3
+FG_ERR_WORKSPACE = 4
+FG_ERR_LAUNCH = 5
+
+EXPORTS = ["fg_status_string", "fg_auto_n_bins", "fg_workspace_size", "fg_bin_points",
+           "fg_binned_select_knn", "fg_binned_select_knn_counted", "fg_query_binned",
+           "fg_knn_backward"]
+
+
+class FgError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s" % (where, status_string(status)))
+
+
+class _Binning(ctypes.Structure):
+    _fields_ = [("bin_idx", ctypes.c_void_p), ("perm", ctypes.c_void_p),
+                ("bin_bounds", ctypes.c_void_p), ("sorted_soa", ctypes.c_void_p),
+                ("seg_geom", ctypes.c_void_p), ("soa_stride", ctypes.c_int64),
+                ("cells_per_segment", ctypes.c_int64), ("n_bins", ctypes.c_int32),
+                ("d_bin", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library; build it first if it is not there (never falls back to a CPU path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        L.fg_status_string.restype = ctypes.c_char_p
+        L.fg_status_string.argtypes = [ctypes.c_int]
+        L.fg_auto_n_bins.restype = ctypes.c_int
+        L.fg_auto_n_bins.argtypes = [i64, i32, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.fg_workspace_size.restype = ctypes.c_int
+        L.fg_workspace_size.argtypes = [i64, i32, i32, i32, i32, i32, ctypes.POINTER(sz)]
+        L.fg_bin_points.restype = ctypes.c_int
+        L.fg_bin_points.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, sz,
+                                    ctypes.POINTER(_Binning), vp]
+        L.fg_binned_select_knn.restype = ctypes.c_int
+        L.fg_binned_select_knn.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.fg_binned_select_knn_counted.restype = ctypes.c_int
+        L.fg_binned_select_knn_counted.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp,
+                                                   vp, sz, vp]
+        L.fg_query_binned.restype = ctypes.c_int
+        L.fg_query_binned.argtypes = [ctypes.POINTER(_Binning), vp, i64, i32, i32, i32, vp, vp, vp, vp]
+        L.fg_knn_backward.restype = ctypes.c_int
+        L.fg_knn_backward.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().fg_status_string(int(status)).decode()
+
+
+fg_status_string = status_string
+
+
+def _check(status: int, where: str):
+    if status != FG_OK:
+        raise FgError(status, where)
+
+
+def _stream() -> int:
+    return int(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError("%s must be a device tensor" % name)
+    if t.dtype != dtype or not t.is_contiguous():
+        raise ValueError("%s must be contiguous %s" % (name, dtype))
+    return t
+
+
+def _ptr(t) -> int:
+    return 0 if t is None or t.numel() == 0 else int(t.data_ptr())
+
+
+def fg_auto_n_bins(n: int, n_segments: int, k: int, d: int, mode: int = 1):
+    nb, db = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().fg_auto_n_bins(n, n_segments, k, d, mode, ctypes.byref(nb), ctypes.byref(db)),
+           "fg_auto_n_bins")
+    return int(nb.value), int(db.value)
+
+
+def fg_workspace_size(n: int, d: int, n_segments: int, k: int, n_bins: int = 0, d_bin: int = 0) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().fg_workspace_size(n, d, n_segments, k, n_bins, d_bin, ctypes.byref(out)),
+           "fg_workspace_size")
+    return int(out.value)
+
+
+def alloc_workspace(n: int, d: int, n_segments: int, k: int, n_bins: int = 0, d_bin: int = 0,
+                    device="cuda") -> torch.Tensor:
+    size = fg_workspace_size(n, d, n_segments, k, n_bins, d_bin)
+    return torch.empty(max(size, 256), dtype=torch.uint8, device=device)
+
+
+@dataclass
+class Binning:
+    """Views into the workspace (kept alive here) produced by fg_bin_points."""
+    raw: _Binning
+    workspace: torch.Tensor
+    n: int
+    d: int
+    n_segments: int
+    n_bins: int
+    d_bin: int
+    cells_per_segment: int
+    soa_stride: int
+
+    def _view(self, ptr: int, count: int, dtype) -> torch.Tensor:
+        off = ptr - self.workspace.data_ptr()
+        nbytes = count * torch.empty((), dtype=dtype).element_size()
+        return self.workspace[off:off + nbytes].view(dtype)
+
+    @property
+    def bin_idx(self):
+        return self._view(self.raw.bin_idx, self.n, torch.int32)
+
+    @property
+    def perm(self):
+        return self._view(self.raw.perm, self.n, torch.int32)
+
+    @property
+    def bin_bounds(self):
+        return self._view(self.raw.bin_bounds, self.n_segments * self.cells_per_segment + 1, torch.int32)
+
+    @property
+    def sorted_soa(self):
+        return self._view(self.raw.sorted_soa, self.d * self.soa_stride, torch.float32).view(self.d, self.soa_stride)
+
+    @property
+    def seg_geom(self):
+        return self._view(self.raw.seg_geom, self.n_segments * self.d_bin * 4, torch.float32).view(
+            self.n_segments, self.d_bin, 4)
+
+
+def fg_bin_points(coords: torch.Tensor, row_splits: torch.Tensor, k_hint: int, n_bins: int = 0,
+                  d_bin: int = 0, workspace: torch.Tensor | None = None) -> Binning:
+    coords = _dev(coords, torch.float32, "coords")
+    row_splits = _dev(row_splits, torch.int32, "row_splits")
+    n, d = coords.shape
+    s = row_splits.numel() - 1
+    if workspace is None:
+        workspace = alloc_workspace(n, d, s, k_hint, n_bins, d_bin, coords.device)
+    raw = _Binning()
+    _check(lib().fg_bin_points(_ptr(coords), _ptr(row_splits), n, d, s, k_hint, n_bins, d_bin,
+                               _ptr(workspace), workspace.numel(), ctypes.byref(raw), _stream()),
+           "fg_bin_points")
+    return Binning(raw, workspace, n, d, s, int(raw.n_bins), int(raw.d_bin),
+                   int(raw.cells_per_segment), int(raw.soa_stride))
+
+
+def fg_query_binned(binning: Binning, row_splits: torch.Tensor, k: int, out_idx=None, out_d2=None,
+                    out_candidates=None):
+    row_splits = _dev(row_splits, torch.int32, "row_splits")
+    n = binning.n
+    dev = binning.workspace.device
+    if out_idx is None:
+        out_idx = torch.empty((n, k), dtype=torch.int32, device=dev)
+    if out_d2 is None:
+        out_d2 = torch.empty((n, k), dtype=torch.float32, device=dev)
+    _check(lib().fg_query_binned(ctypes.byref(binning.raw), _ptr(row_splits), n, binning.d,
+                                 binning.n_segments, k, _ptr(out_idx), _ptr(out_d2),
+                                 _ptr(out_candidates), _stream()), "fg_query_binned")
+    return out_idx, out_d2
+
+
+def fg_binned_select_knn(coords: torch.Tensor, row_splits: torch.Tensor, k: int, n_bins: int = 0,
+                         d_bin: int = 0, workspace: torch.Tensor | None = None, out_idx=None,
+                         out_d2=None):
+    coords = _dev(coords, torch.float32, "coords")
+    row_splits = _dev(row_splits, torch.int32, "row_splits")
+    n, d = coords.shape
+    s = row_splits.numel() - 1
+    if workspace is None:
+        workspace = alloc_workspace(n, d, s, k, n_bins, d_bin, coords.device)
+    if out_idx is None:
+        out_idx = torch.empty((n, k), dtype=torch.int32, device=coords.device)
+    if out_d2 is None:
+        out_d2 = torch.empty((n, k), dtype=torch.float32, device=coords.device)
+    _check(lib().fg_binned_select_knn(_ptr(coords), _ptr(row_splits), n, d, s, k, n_bins, d_bin,
+                                      _ptr(out_idx), _ptr(out_d2), _ptr(workspace),
+                                      workspace.numel(), _stream()), "fg_binned_select_knn")
+    return out_idx, out_d2
+
+
+def fg_binned_select_knn_counted(coords: torch.Tensor, row_splits: torch.Tensor, k: int,
+                                 n_bins: int = 0, d_bin: int = 0,
+                                 workspace: torch.Tensor | None = None):
+    coords = _dev(coords, torch.float32, "coords")
+    row_splits = _dev(row_splits, torch.int32, "row_splits")
+    n, d = coords.shape
+    s = row_splits.numel() - 1
+    if workspace is None:
+        workspace = alloc_workspace(n, d, s, k, n_bins, d_bin, coords.device)
+    out_idx = torch.empty((n, k), dtype=torch.int32, device=coords.device)
+    out_d2 = torch.empty((n, k), dtype=torch.float32, device=coords.device)
+    cand = torch.empty((n,), dtype=torch.int32, device=coords.device)
+    _check(lib().fg_binned_select_knn_counted(_ptr(coords), _ptr(row_splits), n, d, s, k, n_bins,
+                                              d_bin, _ptr(out_idx), _ptr(out_d2), _ptr(cand),
+                                              _ptr(workspace), workspace.numel(), _stream()),
+           "fg_binned_select_knn_counted")
+    return out_idx, out_d2, cand
+
+
+def fg_knn_backward(grad_d2: torch.Tensor, idx: torch.Tensor, coords: torch.Tensor,
+                    grad_coords: torch.Tensor | None = None) -> torch.Tensor:
+    grad_d2 = _dev(grad_d2, torch.float32, "grad_d2")
+    idx = _dev(idx, torch.int32, "idx")
+    coords = _dev(coords, torch.float32, "coords")
+    n, d = coords.shape
+    k = idx.shape[1]
+    if tuple(grad_d2.shape) != (n, k) or idx.shape[0] != n:
+        raise ValueError("grad_d2 and idx must be [n, k]")
+    if grad_coords is None:
+        grad_coords = torch.empty((n, d), dtype=torch.float32, device=coords.device)
+    _check(lib().fg_knn_backward(_ptr(grad_d2), _ptr(idx), _ptr(coords), n, d, k, _ptr(grad_coords),
+                                 None, 0, _stream()), "fg_knn_backward")
+    return grad_coords

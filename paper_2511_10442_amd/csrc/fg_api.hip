@@ -1,0 +1,273 @@
+// C-ABI entry points: argument validation, workspace layout, stage launches.
+#include <math.h>
+#include "fg_internal.hpp"
+
+namespace fg {
+
+hipError_t launch_query_d2(const QueryArgs&, int32_t, hipStream_t);
+hipError_t launch_query_d3(const QueryArgs&, int32_t, hipStream_t);
+hipError_t launch_query_d4(const QueryArgs&, int32_t, hipStream_t);
+hipError_t launch_query_d5(const QueryArgs&, int32_t, hipStream_t);
+hipError_t launch_query_d6(const QueryArgs&, int32_t, hipStream_t);
+hipError_t launch_query_d7(const QueryArgs&, int32_t, hipStream_t);
+hipError_t launch_query_d8(const QueryArgs&, int32_t, hipStream_t);
+hipError_t launch_query_d9(const QueryArgs&, int32_t, hipStream_t);
+hipError_t launch_query_d10(const QueryArgs&, int32_t, hipStream_t);
+
+hipError_t launch_query(const QueryArgs& a, int32_t d, int32_t d_bin, hipStream_t stream)
+{
+    switch (d) {
+        case 2: return launch_query_d2(a, d_bin, stream);
+        case 3: return launch_query_d3(a, d_bin, stream);
+        case 4: return launch_query_d4(a, d_bin, stream);
+        case 5: return launch_query_d5(a, d_bin, stream);
+        case 6: return launch_query_d6(a, d_bin, stream);
+        case 7: return launch_query_d7(a, d_bin, stream);
+        case 8: return launch_query_d8(a, d_bin, stream);
+        case 9: return launch_query_d9(a, d_bin, stream);
+        case 10: return launch_query_d10(a, d_bin, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+namespace {
+
+constexpr size_t kAlign = 256;
+
+// fg_auto_n_bins mode 1: cells per row split = kTunedCellsPerK * n_elems / K, i.e. about
+// K / kTunedCellsPerK points per bin, over the first min(d, kTunedMaxDBin) dimensions.
+constexpr double kTunedCellsPerK = 8.0;
+constexpr int32_t kTunedMaxDBin = 3;
+constexpr int32_t kTunedMaxBins = 256;
+constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Layout {
+    size_t keys, geom, bin_idx, rank, perm, soa, bounds, partials, total;
+    int64_t soa_stride, total_bins, cells_per_segment;
+};
+
+// n_bins, d_bin already resolved and validated
+Layout make_layout(int64_t n, int32_t d, int32_t n_segments, int32_t n_bins, int32_t d_bin)
+{
+    Layout L;
+    int64_t cells = 1;
+    for (int c = 0; c < d_bin; ++c) cells *= n_bins;
+    L.cells_per_segment = cells;
+    L.total_bins = cells * n_segments;
+    L.soa_stride = (n + 63) / 64 * 64;
+    size_t off = 0;
+    L.keys = off;     off = align_up(off + sizeof(uint32_t) * 2 * (size_t)n_segments * d_bin);
+    L.geom = off;     off = align_up(off + sizeof(float) * kGeomStride * (size_t)n_segments * d_bin);
+    L.bin_idx = off;  off = align_up(off + sizeof(int32_t) * (size_t)n);
+    L.rank = off;     off = align_up(off + sizeof(int32_t) * (size_t)n);
+    L.perm = off;     off = align_up(off + sizeof(int32_t) * (size_t)n);
+    L.soa = off;      off = align_up(off + sizeof(float) * (size_t)L.soa_stride * d);
+    L.bounds = off;   off = align_up(off + sizeof(int32_t) * (size_t)(L.total_bins + 1));
+    L.partials = off; off = align_up(off + sizeof(int32_t) * (size_t)((L.total_bins + 1 + kScanChunkHost - 1) / kScanChunkHost));
+    L.total = off;
+    return L;
+}
+
+fg_status check_problem(int64_t n, int32_t d, int32_t n_segments, int32_t k)
+{
+    if (n < 0 || n >= ((int64_t)1 << 31) || n_segments < 1 || k < 1) return FG_ERR_BAD_SHAPE;
+    if (d < FG_MIN_D || d > FG_MAX_D || k > FG_MAX_K) return FG_ERR_UNSUPPORTED;
+    return FG_OK;
+}
+
+// fills in automatic values, validates explicit ones
+fg_status resolve_bins(int64_t n, int32_t d, int32_t n_segments, int32_t k, int32_t* n_bins, int32_t* d_bin)
+{
+    int32_t auto_n = 0, auto_db = 0;
+    fg_status st = fg_auto_n_bins(n, n_segments, k, d, 1, &auto_n, &auto_db);
+    if (st != FG_OK) return st;
+    if (*d_bin <= 0) {
+        *d_bin = auto_db;
+        if (*n_bins > 0) {   // explicit n_bins with automatic d_bin: keep the bin table within bounds
+            while (*d_bin > FG_MIN_D_BIN && pow((double)*n_bins, *d_bin) * n_segments > (double)FG_MAX_TOTAL_BINS) --*d_bin;
+        }
+    }
+    if (*d_bin < FG_MIN_D_BIN || *d_bin > FG_MAX_D_BIN || *d_bin > d) return FG_ERR_UNSUPPORTED;
+    if (*n_bins <= 0) {
+        if (*d_bin == auto_db) *n_bins = auto_n;
+        else {   // explicit d_bin with automatic n_bins: same occupancy target over d_bin dimensions
+            double cells = pow((double)auto_n, auto_db);
+            int32_t v = (int32_t)floor(pow(cells, 1.0 / *d_bin) + 1e-9);
+            *n_bins = v < 1 ? 1 : v;
+        }
+    }
+    double total = pow((double)*n_bins, *d_bin) * n_segments;
+    if (*n_bins < 1 || total > (double)FG_MAX_TOTAL_BINS) return FG_ERR_BAD_SHAPE;
+    return FG_OK;
+}
+
+}  // namespace
+}  // namespace fg
+
+using namespace fg;
+
+extern "C" {
+
+const char* fg_status_string(fg_status status)
+{
+    switch (status) {
+        case FG_OK: return "FG_OK";
+        case FG_ERR_NULL: return "FG_ERR_NULL: a required pointer is NULL";
+        case FG_ERR_BAD_SHAPE: return "FG_ERR_BAD_SHAPE: size or bin count out of range";
+        case FG_ERR_UNSUPPORTED: return "FG_ERR_UNSUPPORTED: d, k or d_bin outside the supported range";
+        case FG_ERR_WORKSPACE: return "FG_ERR_WORKSPACE: workspace too small or misaligned";
+        case FG_ERR_LAUNCH: return "FG_ERR_LAUNCH: HIP launch failed";
+        default: return "unknown fg_status";
+    }
+}
+
+fg_status fg_auto_n_bins(int64_t n, int32_t n_segments, int32_t k, int32_t d, int32_t mode,
+                         int32_t* n_bins, int32_t* d_bin)
+{
+    if (!n_bins || !d_bin) return FG_ERR_NULL;
+    fg_status st = check_problem(n, d, n_segments, k);
+    if (st != FG_OK) return st;
+    if (mode != 0 && mode != 1) return FG_ERR_BAD_SHAPE;
+    const double n_elems = (double)n / (double)n_segments;
+    if (mode == 0) {
+        // Section 3: (32 n_elems / K)^(1/d_max), clamped to [5, 30]; at most the first 5 dimensions
+        const int32_t db = d < 5 ? d : 5;
+        double x = n_elems > 0 ? pow(32.0 * n_elems / (double)k, 1.0 / db) : 0.0;
+        int32_t v = (int32_t)floor(x + 1e-9);
+        v = v < 5 ? 5 : (v > 30 ? 30 : v);
+        while (db > 0 && pow((double)v, db) * n_segments > (double)FG_MAX_TOTAL_BINS && v > 1) --v;
+        *n_bins = v;
+        *d_bin = db;
+        return FG_OK;
+    }
+    // mode 1: same functional form, this build's constants (kTunedCellsPerK, kTunedMaxDBin, kTunedMaxBins)
+    const int32_t db = d < kTunedMaxDBin ? d : kTunedMaxDBin;
+    double cells = n_elems > 0 ? kTunedCellsPerK * n_elems / (double)k : 1.0;
+    double x = pow(cells, 1.0 / db);
+    int32_t v = (int32_t)floor(x + 1e-9);
+    v = v < 1 ? 1 : (v > kTunedMaxBins ? kTunedMaxBins : v);
+    while (pow((double)v, db) * n_segments > (double)FG_MAX_TOTAL_BINS && v > 1) --v;
+    *n_bins = v;
+    *d_bin = db;
+    return FG_OK;
+}
+
+fg_status fg_workspace_size(int64_t n, int32_t d, int32_t n_segments, int32_t k,
+                            int32_t n_bins, int32_t d_bin, size_t* bytes)
+{
+    if (!bytes) return FG_ERR_NULL;
+    fg_status st = check_problem(n, d, n_segments, k);
+    if (st != FG_OK) return st;
+    st = resolve_bins(n, d, n_segments, k, &n_bins, &d_bin);
+    if (st != FG_OK) return st;
+    *bytes = make_layout(n, d, n_segments, n_bins, d_bin).total;
+    return FG_OK;
+}
+
+fg_status fg_bin_points(const float* coords, const int32_t* row_splits, int64_t n, int32_t d,
+                        int32_t n_segments, int32_t k_hint, int32_t n_bins, int32_t d_bin,
+                        void* workspace, size_t workspace_bytes, fg_binning* view, void* stream)
+{
+    if (!view) return FG_ERR_NULL;
+    fg_status st = check_problem(n, d, n_segments, k_hint);
+    if (st != FG_OK) return st;
+    st = resolve_bins(n, d, n_segments, k_hint, &n_bins, &d_bin);
+    if (st != FG_OK) return st;
+    if (!coords && n > 0) return FG_ERR_NULL;
+    if (!row_splits || !workspace) return FG_ERR_NULL;
+    const Layout L = make_layout(n, d, n_segments, n_bins, d_bin);
+    if (((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < L.total) return FG_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    view->bin_idx = (const int32_t*)(ws + L.bin_idx);
+    view->perm = (const int32_t*)(ws + L.perm);
+    view->bin_bounds = (const int32_t*)(ws + L.bounds);
+    view->sorted_soa = (const float*)(ws + L.soa);
+    view->seg_geom = (const float*)(ws + L.geom);
+    view->soa_stride = L.soa_stride;
+    view->cells_per_segment = L.cells_per_segment;
+    view->n_bins = n_bins;
+    view->d_bin = d_bin;
+    if (n == 0) return FG_OK;
+    hipError_t e = launch_binning(coords, row_splits, (int32_t)n, d, n_segments, n_bins, d_bin, L.total_bins,
+                                  (uint32_t*)(ws + L.keys), (float*)(ws + L.geom), (int32_t*)(ws + L.bin_idx),
+                                  (int32_t*)(ws + L.rank), (int32_t*)(ws + L.perm), (float*)(ws + L.soa),
+                                  L.soa_stride, (int32_t*)(ws + L.bounds), (int32_t*)(ws + L.partials),
+                                  (hipStream_t)stream);
+    return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
+}
+
+fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int64_t n, int32_t d,
+                          int32_t n_segments, int32_t k, int32_t* out_idx, float* out_d2,
+                          int32_t* out_candidates, void* stream)
+{
+    if (!view) return FG_ERR_NULL;
+    fg_status st = check_problem(n, d, n_segments, k);
+    if (st != FG_OK) return st;
+    if (n == 0) return FG_OK;
+    if (!row_splits || !out_idx || !out_d2 || !view->perm || !view->bin_bounds || !view->sorted_soa ||
+        !view->seg_geom)
+        return FG_ERR_NULL;
+    if (view->d_bin < FG_MIN_D_BIN || view->d_bin > FG_MAX_D_BIN || view->d_bin > d) return FG_ERR_UNSUPPORTED;
+    if (view->n_bins < 1 || view->cells_per_segment < 1 ||
+        view->cells_per_segment * (int64_t)n_segments > FG_MAX_TOTAL_BINS || view->soa_stride < n)
+        return FG_ERR_BAD_SHAPE;
+    QueryArgs a;
+    a.soa = view->sorted_soa; a.perm = view->perm; a.bounds = view->bin_bounds; a.geom = view->seg_geom;
+    a.row_splits = row_splits; a.out_idx = out_idx; a.out_d2 = out_d2; a.out_cand = out_candidates;
+    a.soa_stride = view->soa_stride; a.n = (int32_t)n; a.n_segments = n_segments; a.k = k;
+    a.n_bins = view->n_bins; a.cells_per_segment = (int32_t)view->cells_per_segment;
+    hipError_t e = launch_query(a, d, view->d_bin, (hipStream_t)stream);
+    return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
+}
+
+static fg_status knn_impl(const float* coords, const int32_t* row_splits, int64_t n, int32_t d, int32_t n_segments,
+                          int32_t k, int32_t n_bins, int32_t d_bin, int32_t* out_idx, float* out_d2,
+                          int32_t* out_candidates, void* workspace, size_t workspace_bytes, void* stream)
+{
+    fg_status st = check_problem(n, d, n_segments, k);
+    if (st != FG_OK) return st;
+    if (n == 0) return FG_OK;
+    if (!out_idx || !out_d2) return FG_ERR_NULL;
+    fg_binning view;
+    st = fg_bin_points(coords, row_splits, n, d, n_segments, k, n_bins, d_bin, workspace, workspace_bytes, &view,
+                       stream);
+    if (st != FG_OK) return st;
+    return fg_query_binned(&view, row_splits, n, d, n_segments, k, out_idx, out_d2, out_candidates, stream);
+}
+
+fg_status fg_binned_select_knn(const float* coords, const int32_t* row_splits, int64_t n,
+                               int32_t d, int32_t n_segments, int32_t k, int32_t n_bins,
+                               int32_t d_bin, int32_t* out_idx, float* out_d2,
+                               void* workspace, size_t workspace_bytes, void* stream)
+{
+    return knn_impl(coords, row_splits, n, d, n_segments, k, n_bins, d_bin, out_idx, out_d2, nullptr, workspace,
+                    workspace_bytes, stream);
+}
+
+fg_status fg_binned_select_knn_counted(const float* coords, const int32_t* row_splits, int64_t n,
+                                       int32_t d, int32_t n_segments, int32_t k, int32_t n_bins,
+                                       int32_t d_bin, int32_t* out_idx, float* out_d2,
+                                       int32_t* out_candidates,
+                                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!out_candidates && n > 0) return FG_ERR_NULL;
+    return knn_impl(coords, row_splits, n, d, n_segments, k, n_bins, d_bin, out_idx, out_d2, out_candidates,
+                    workspace, workspace_bytes, stream);
+}
+
+fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float* coords,
+                          int64_t n, int32_t d, int32_t k, float* grad_coords,
+                          void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace; (void)workspace_bytes;
+    fg_status st = check_problem(n, d, 1, k);
+    if (st != FG_OK) return st;
+    if (n == 0) return FG_OK;
+    if (!grad_d2 || !idx || !coords || !grad_coords) return FG_ERR_NULL;
+    hipError_t e = launch_backward(grad_d2, idx, coords, (int32_t)n, d, k, grad_coords, (hipStream_t)stream);
+    return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,310 @@
+// Spatial partition + counting sort (paper Section 3: bin assignment per row split, points
+// sorted by bin, cumulative bin boundaries).  gfx950, wave64.
+//
+// Stages, all enqueued on one stream:
+//   prepare   zero the bin counters, reset the bounding-box keys
+//   bbox      per row split, min/max of the first d_bin coordinates (wave reduction + one
+//             atomic per wave and dimension on an order-preserving integer key)
+//   geometry  per (row split, dim): lower edge, bins per unit length, bin width, rounding slack
+//   assign    flat bin of every point + its arrival rank inside the bin (returning atomic)
+//   scan      exclusive prefix over the counters (partials / tops / apply)
+//   scatter   sorted position = bounds[bin] + rank: write perm and the bin-ordered SoA coords
+#include "fg_internal.hpp"
+
+namespace fg {
+
+constexpr int kBlock = 256;
+constexpr int kScanItems = 16;                    // counters per thread in the scan kernels
+constexpr int kScanChunk = kBlock * kScanItems;   // counters per block
+
+__device__ __forceinline__ uint32_t float_to_key(float f)
+{
+    uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float key_to_float(uint32_t k)
+{
+    uint32_t b = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    return __uint_as_float(b);
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_prepare(int32_t* __restrict__ counters, int64_t n_counters, uint32_t* __restrict__ bbox_keys, int32_t n_keys)
+{
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    int64_t step = (int64_t)gridDim.x * kBlock;
+    for (int64_t j = i; j < n_counters; j += step) counters[j] = 0;
+    // keys: [S][d_bin] minima then [S][d_bin] maxima
+    for (int64_t j = i; j < 2 * (int64_t)n_keys; j += step) bbox_keys[j] = (j < n_keys) ? 0xffffffffu : 0u;
+}
+
+__device__ __forceinline__ float wave_min(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+
+// One point per thread.  A wave whose lanes all sit in one row split reduces in registers and
+// issues one atomic pair per dimension; a wave straddling a split boundary falls back to
+// per-lane atomics.
+template <int DB>
+__global__ void __launch_bounds__(kBlock)
+k_bbox(const float* __restrict__ coords, const int32_t* __restrict__ row_splits, int32_t n, int32_t d,
+       int32_t n_segments, uint32_t* __restrict__ bbox_keys)
+{
+    int32_t i = blockIdx.x * kBlock + threadIdx.x;
+    bool live = i < n;
+    int32_t ii = live ? i : n - 1;
+    int32_t s = segment_of(row_splits, n_segments, ii);
+    int32_t s0 = __shfl(s, 0, 64);
+    bool uniform = __all(s == s0);
+    uint32_t* kmin = bbox_keys;
+    uint32_t* kmax = bbox_keys + (int64_t)n_segments * DB;
+    const float* p = coords + (int64_t)ii * d;
+#pragma unroll
+    for (int c = 0; c < DB; ++c) {
+        float x = p[c];
+        if (uniform) {
+            float mn = wave_min(x), mx = wave_max(x);   // dead lanes duplicate point n-1: harmless
+            if ((threadIdx.x & 63) == 0) {
+                atomicMin(&kmin[s * DB + c], float_to_key(mn));
+                atomicMax(&kmax[s * DB + c], float_to_key(mx));
+            }
+        } else if (live) {
+            atomicMin(&kmin[s * DB + c], float_to_key(x));
+            atomicMax(&kmax[s * DB + c], float_to_key(x));
+        }
+    }
+}
+
+// geom[s][c] = { lo, inv_w, w, slack }.
+//   inv_w = n_bins / (hi - lo) bins per unit length; 0 marks a dimension in which every point of
+//           the row split lands in bin 0 (zero, denormal-small or non-finite extent, empty split).
+//   slack  bounds |true bin threshold - (lo + j*w)| from above: the float32 evaluation of
+//           floor((x-lo)*inv_w) and of lo + j*w together err by < 2^-21 * max(|lo|,|hi|,hi-lo).
+__global__ void __launch_bounds__(kBlock)
+k_geometry(const uint32_t* __restrict__ bbox_keys, int32_t n_keys, int32_t n_bins, float* __restrict__ geom)
+{
+    int32_t t = blockIdx.x * kBlock + threadIdx.x;
+    if (t >= n_keys) return;
+    float lo = key_to_float(bbox_keys[t]);
+    float hi = key_to_float(bbox_keys[n_keys + t]);
+    float ext = hi - lo;
+    float inv_w = 0.0f, w = 0.0f, slack = 0.0f;
+    if (ext >= 1e-30f && ext <= 3.0e38f) {          // false for NaN and for the empty-split sentinels
+        float iw = (float)n_bins / ext;
+        if (iw <= 3.0e38f) {
+            inv_w = iw;
+            w = ext / (float)n_bins;
+            slack = 9.5367431640625e-07f * fmaxf(fmaxf(fabsf(lo), fabsf(hi)), ext);   // 2^-20
+        }
+    }
+    if (!(lo >= -3.0e38f && lo <= 3.0e38f)) lo = 0.0f;   // empty split: keep the record finite
+    float* g = geom + (int64_t)t * kGeomStride;
+    g[0] = lo; g[1] = inv_w; g[2] = w; g[3] = slack;
+}
+
+template <int DB>
+__global__ void __launch_bounds__(kBlock)
+k_assign(const float* __restrict__ coords, const int32_t* __restrict__ row_splits, int32_t n, int32_t d,
+         int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, const float* __restrict__ geom,
+         int32_t* __restrict__ bin_idx, int32_t* __restrict__ rank, int32_t* __restrict__ counters)
+{
+    int32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    int32_t s = segment_of(row_splits, n_segments, i);
+    const float* p = coords + (int64_t)i * d;
+    const float* g = geom + (int64_t)s * DB * kGeomStride;
+    int32_t flat = 0;
+#pragma unroll
+    for (int c = 0; c < DB; ++c)
+        flat = flat * n_bins + cell_of(p[c], g[c * kGeomStride + 0], g[c * kGeomStride + 1], n_bins);
+    flat += s * cells_per_segment;
+    bin_idx[i] = flat;
+    rank[i] = atomicAdd(&counters[flat], 1);
+}
+
+// ---- exclusive scan over the counters, in place: counters[b] -> first sorted position of bin b.
+__device__ __forceinline__ int32_t wave_incl_scan(int32_t v)
+{
+    int lane = threadIdx.x & 63;
+    for (int o = 1; o < 64; o <<= 1) {
+        int32_t t = __shfl_up(v, o, 64);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+// block-wide exclusive scan of one value per thread; returns the exclusive prefix, total in *total
+__device__ __forceinline__ int32_t block_excl_scan(int32_t v, int32_t* total)
+{
+    __shared__ int32_t wave_tot[kBlock / 64];
+    int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    int32_t inc = wave_incl_scan(v);
+    if (lane == 63) wave_tot[wv] = inc;
+    __syncthreads();
+    int32_t base = 0, tot = 0;
+#pragma unroll
+    for (int j = 0; j < kBlock / 64; ++j) {
+        int32_t t = wave_tot[j];
+        if (j < wv) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_scan_partials(const int32_t* __restrict__ counters, int64_t n_counters, int32_t* __restrict__ partials)
+{
+    int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kScanItems;
+    int32_t sum = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        int64_t q = base + j;
+        if (q < n_counters) sum += counters[q];
+    }
+    int32_t total;
+    block_excl_scan(sum, &total);
+    if (threadIdx.x == 0) partials[blockIdx.x] = total;
+}
+
+// single block: exclusive scan of the per-chunk totals, in place
+__global__ void __launch_bounds__(kBlock)
+k_scan_tops(int32_t* __restrict__ partials, int32_t n_partials)
+{
+    int32_t carry = 0;
+    for (int32_t b = 0; b < n_partials; b += kBlock) {
+        int32_t q = b + threadIdx.x;
+        int32_t v = q < n_partials ? partials[q] : 0;
+        int32_t total;
+        int32_t ex = block_excl_scan(v, &total);
+        if (q < n_partials) partials[q] = carry + ex;
+        carry += total;
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_scan_apply(int32_t* __restrict__ counters, int64_t n_counters, const int32_t* __restrict__ partials)
+{
+    int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kScanItems;
+    int32_t v[kScanItems];
+    int32_t sum = 0;
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        int64_t q = base + j;
+        v[j] = q < n_counters ? counters[q] : 0;
+        sum += v[j];
+    }
+    int32_t total;
+    int32_t run = block_excl_scan(sum, &total) + partials[blockIdx.x];
+#pragma unroll
+    for (int j = 0; j < kScanItems; ++j) {
+        int64_t q = base + j;
+        if (q < n_counters) counters[q] = run;
+        run += v[j];
+    }
+}
+
+template <int D>
+__global__ void __launch_bounds__(kBlock)
+k_scatter(const float* __restrict__ coords, int32_t n, const int32_t* __restrict__ bin_idx,
+          const int32_t* __restrict__ rank, const int32_t* __restrict__ bounds,
+          int32_t* __restrict__ perm, float* __restrict__ soa, int64_t soa_stride)
+{
+    int32_t i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= n) return;
+    int32_t pos = bounds[bin_idx[i]] + rank[i];
+    perm[pos] = i;
+    const float* p = coords + (int64_t)i * D;
+#pragma unroll
+    for (int c = 0; c < D; ++c) soa[(int64_t)c * soa_stride + pos] = p[c];
+}
+
+template <int DB>
+static void launch_bbox_assign(bool assign, const float* coords, const int32_t* row_splits, int32_t n, int32_t d,
+                               int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, uint32_t* bbox_keys,
+                               const float* geom, int32_t* bin_idx, int32_t* rank, int32_t* counters,
+                               hipStream_t stream)
+{
+    int grid = (n + kBlock - 1) / kBlock;
+    if (!assign)
+        hipLaunchKernelGGL(k_bbox<DB>, dim3(grid), dim3(kBlock), 0, stream, coords, row_splits, n, d, n_segments,
+                           bbox_keys);
+    else
+        hipLaunchKernelGGL(k_assign<DB>, dim3(grid), dim3(kBlock), 0, stream, coords, row_splits, n, d, n_segments,
+                           n_bins, cells_per_segment, geom, bin_idx, rank, counters);
+}
+
+template <int D>
+static void launch_scatter(const float* coords, int32_t n, const int32_t* bin_idx, const int32_t* rank,
+                           const int32_t* bounds, int32_t* perm, float* soa, int64_t soa_stride, hipStream_t stream)
+{
+    int grid = (n + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(k_scatter<D>, dim3(grid), dim3(kBlock), 0, stream, coords, n, bin_idx, rank, bounds, perm, soa,
+                       soa_stride);
+}
+
+hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_t n, int32_t d,
+                          int32_t n_segments, int32_t n_bins, int32_t d_bin, int64_t total_bins,
+                          uint32_t* bbox_keys, float* geom, int32_t* bin_idx, int32_t* rank,
+                          int32_t* perm, float* soa, int64_t soa_stride, int32_t* bounds,
+                          int32_t* scan_partials, hipStream_t stream)
+{
+    const int64_t n_counters = total_bins + 1;
+    const int32_t n_keys = n_segments * d_bin;
+    const int32_t cells_per_segment = (int32_t)(total_bins / n_segments);
+    {
+        int64_t work = n_counters > 2 * (int64_t)n_keys ? n_counters : 2 * (int64_t)n_keys;
+        int64_t grid = (work + kBlock - 1) / kBlock;
+        if (grid > 4096) grid = 4096;
+        hipLaunchKernelGGL(k_prepare, dim3((unsigned)grid), dim3(kBlock), 0, stream, bounds, n_counters, bbox_keys,
+                           n_keys);
+    }
+#define FG_DB_SWITCH(ASSIGN)                                                                                       \
+    switch (d_bin) {                                                                                               \
+        case 2: launch_bbox_assign<2>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
+                                      bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
+        case 3: launch_bbox_assign<3>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
+                                      bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
+        case 4: launch_bbox_assign<4>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
+                                      bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
+        case 5: launch_bbox_assign<5>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
+                                      bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
+        default: return hipErrorInvalidValue;                                                                      \
+    }
+    FG_DB_SWITCH(false)
+    hipLaunchKernelGGL(k_geometry, dim3((n_keys + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, bbox_keys, n_keys,
+                       n_bins, geom);
+    FG_DB_SWITCH(true)
+#undef FG_DB_SWITCH
+    {
+        int64_t n_chunks = (n_counters + kScanChunk - 1) / kScanChunk;
+        hipLaunchKernelGGL(k_scan_partials, dim3((unsigned)n_chunks), dim3(kBlock), 0, stream, bounds, n_counters,
+                           scan_partials);
+        hipLaunchKernelGGL(k_scan_tops, dim3(1), dim3(kBlock), 0, stream, scan_partials, (int32_t)n_chunks);
+        hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_chunks), dim3(kBlock), 0, stream, bounds, n_counters,
+                           scan_partials);
+    }
+    switch (d) {
+        case 2: launch_scatter<2>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 3: launch_scatter<3>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 4: launch_scatter<4>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 5: launch_scatter<5>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 6: launch_scatter<6>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 7: launch_scatter<7>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 8: launch_scatter<8>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 9: launch_scatter<9>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 10: launch_scatter<10>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace fg

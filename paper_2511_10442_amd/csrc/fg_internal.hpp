@@ -1,0 +1,65 @@
+// Internal declarations shared by the translation units of libfastgraph_hip.so (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "fastgraph.h"
+
+namespace fg {
+
+constexpr int kGeomStride = 4;   // floats per (segment, binning dim): lo, inv_w, w, slack
+
+// Everything the query stage needs; plain device pointers.
+struct QueryArgs {
+    const float* soa;          // [d][soa_stride] bin-ordered coordinates
+    const int32_t* perm;       // [n] sorted position -> original row
+    const int32_t* bounds;     // [S*T+1]
+    const float* geom;         // [S][d_bin][4]
+    const int32_t* row_splits; // [S+1]
+    int32_t* out_idx;          // [n][k]
+    float* out_d2;             // [n][k]
+    int32_t* out_cand;         // [n] or nullptr
+    int64_t soa_stride;
+    int32_t n;
+    int32_t n_segments;
+    int32_t k;
+    int32_t n_bins;
+    int32_t cells_per_segment;
+};
+
+// Host-side launchers, one per translation unit.  Each returns hipGetLastError() of its launches.
+hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_t n, int32_t d,
+                          int32_t n_segments, int32_t n_bins, int32_t d_bin, int64_t total_bins,
+                          uint32_t* bbox_keys, float* geom, int32_t* bin_idx, int32_t* rank,
+                          int32_t* perm, float* soa, int64_t soa_stride, int32_t* bounds,
+                          int32_t* scan_partials, hipStream_t stream);
+
+// d = 2..10, d_bin = 2..min(d,5)
+hipError_t launch_query(const QueryArgs& a, int32_t d, int32_t d_bin, hipStream_t stream);
+
+hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, int32_t n,
+                           int32_t d, int32_t k, float* grad_coords, hipStream_t stream);
+
+// Segment of a (sorted or original) position: largest s with row_splits[s] <= p, skipping empty
+// segments by construction (row_splits[s+1] > p).
+__device__ __forceinline__ int32_t segment_of(const int32_t* __restrict__ row_splits,
+                                              int32_t n_segments, int32_t p)
+{
+    int32_t lo = 0, hi = n_segments;   // invariant: row_splits[lo] <= p < row_splits[hi]
+    while (hi - lo > 1) {
+        int32_t mid = (lo + hi) >> 1;
+        if (row_splits[mid] <= p) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Bin index of coordinate x in one dimension.  Monotone non-decreasing in x, which is what the
+// search's lower bounds rely on.
+__device__ __forceinline__ int32_t cell_of(float x, float lo, float inv_w, int32_t n_bins)
+{
+    float t = (x - lo) * inv_w;
+    int32_t c = (int32_t)floorf(t);
+    c = c < 0 ? 0 : c;
+    return c > n_bins - 1 ? n_bins - 1 : c;
+}
+
+}  // namespace fg

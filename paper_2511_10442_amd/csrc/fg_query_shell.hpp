@@ -1,0 +1,265 @@
+// General shell-expanding exact query kernel: one lane per query, any shell radius.
+//
+// What it computes (paper Section 3, Algorithm 2): for every point, the K-1 nearest other
+// points of its row split, found by scanning the bins on the surface of the hypercube of
+// Chebyshev radius r = 0, 1, 2, ... around the query's bin (Algorithm 1) until the k-th best
+// squared distance is certified smaller than anything unsearched.  Differences from the
+// paper's kernel, none of which changes what "exact" means:
+//   * the running best list is a max-heap of 64-bit keys (distance bits << 32 | original index)
+//     in LDS, one column per lane, instead of an unsorted buffer with a linear max rescan; the
+//     key order is the strict total order (d2, index), so the result does not depend on the
+//     order candidates arrive in;
+//   * the last binning dimension is walked as contiguous runs of bins (bins adjacent in the
+//     last dimension are adjacent in the sorted point order);
+//   * bins whose box lies farther than the current k-th best are skipped (a lower bound on the
+//     distance to any point of the bin, per dimension, with rounding slack);
+//   * the stop test uses the true distance from the query to the faces of the searched cube
+//     instead of r times the first bin width, and stops at once when the cube covers the grid.
+#pragma once
+#include "fg_internal.hpp"
+
+namespace fg {
+
+constexpr int kQueryBlock = 64;                    // one wavefront per workgroup
+constexpr float kBoundShrink = 0.99999618530273f;  // 1 - 2^-18: covers fp32 rounding of d2 and of the bound
+
+template <int D, int DB, bool COUNT>
+struct ShellSearch {
+    float x[D];
+    float glo[DB], gw[DB], gslack[DB];
+    int32_t cc[DB], neff[DB];
+    uint64_t* heap;   // this lane's column: slot j lives at heap[j * kQueryBlock]
+    const float* __restrict__ soa;
+    const int32_t* __restrict__ perm;
+    const int32_t* __restrict__ bounds;
+    int64_t stride;
+    int32_t n_bins, seg_cell0, self_pos, cap, filled, cand;
+    uint64_t tau;     // worst key kept so far once the heap is full, all-ones before
+
+    __device__ __forceinline__ float tau_d2() const { return __uint_as_float((uint32_t)(tau >> 32)); }
+
+    __device__ __forceinline__ void sift_down(uint64_t key, int32_t size)
+    {
+        int32_t i = 0;
+        for (;;) {
+            int32_t l = 2 * i + 1;
+            if (l >= size) break;
+            uint64_t bk = heap[l * kQueryBlock];
+            int32_t big = l;
+            if (l + 1 < size) {
+                uint64_t rk = heap[(l + 1) * kQueryBlock];
+                if (rk > bk) { bk = rk; big = l + 1; }
+            }
+            if (bk <= key) break;
+            heap[i * kQueryBlock] = bk;
+            i = big;
+        }
+        heap[i * kQueryBlock] = key;
+    }
+
+    __device__ __forceinline__ void offer(uint64_t key)
+    {
+        if (filled < cap) {
+            int32_t i = filled++;
+            while (i > 0) {
+                int32_t parent = (i - 1) >> 1;
+                uint64_t pk = heap[parent * kQueryBlock];
+                if (pk >= key) break;
+                heap[i * kQueryBlock] = pk;
+                i = parent;
+            }
+            heap[i * kQueryBlock] = key;
+            if (filled == cap) tau = heap[0];
+        } else if (key < tau) {
+            sift_down(key, cap);
+            tau = heap[0];
+        }
+    }
+
+    // all points at sorted positions [a, b)
+    __device__ __forceinline__ void scan_points(int32_t a, int32_t b)
+    {
+        for (int32_t q = a; q < b; ++q) {
+            if (q == self_pos) continue;
+            float diff = x[0] - soa[q];
+            float d2 = diff * diff;
+#pragma unroll
+            for (int c = 1; c < D; ++c) {
+                diff = x[c] - soa[(int64_t)c * stride + q];
+                d2 = d2 + diff * diff;
+            }
+            if (COUNT) ++cand;
+            uint32_t bits = __float_as_uint(d2);
+            if (bits > (uint32_t)(tau >> 32)) continue;
+            uint64_t key = ((uint64_t)bits << 32) | (uint32_t)perm[q];
+            offer(key);
+        }
+    }
+
+    // true when no point of a box at squared lower-bound distance b2 can enter the best list
+    __device__ __forceinline__ bool cannot_improve(float b2) const
+    {
+        return filled == cap && b2 > 1e-30f && tau_d2() < b2 * kBoundShrink;
+    }
+
+    // lower bound (>= 0) on |x_c - y_c| for any point y whose bin index in dimension c is j = cc[c] + o
+    __device__ __forceinline__ float gap(int c, int32_t j, int32_t o) const
+    {
+        if (o == 0) return 0.0f;
+        float g = (o > 0) ? (glo[c] + (float)j * gw[c]) - x[c] : x[c] - (glo[c] + (float)(j + 1) * gw[c]);
+        g -= gslack[c];
+        return g > 0.0f ? g : 0.0f;
+    }
+
+    template <int LVL>
+    __device__ __forceinline__ void visit(int32_t r, int32_t flat, float partial, bool surf)
+    {
+        const int32_t c0 = cc[LVL];
+        if constexpr (LVL < DB - 1) {
+            int32_t o_lo = -r < -c0 ? -c0 : -r;
+            int32_t o_hi = r > neff[LVL] - 1 - c0 ? neff[LVL] - 1 - c0 : r;
+            for (int32_t o = o_lo; o <= o_hi; ++o) {
+                float g = gap(LVL, c0 + o, o);
+                float p2 = partial + g * g;
+                if (cannot_improve(p2)) continue;
+                bool on = surf || o == r || o == -r;
+                visit<LVL + 1>(r, flat * n_bins + c0 + o, p2, on);
+            }
+        } else {
+            const int32_t row = seg_cell0 + flat * n_bins;
+            if (surf) {   // the whole run of the last dimension belongs to this shell
+                int32_t za = c0 - r < 0 ? 0 : c0 - r;
+                int32_t zb = c0 + r > neff[LVL] - 1 ? neff[LVL] - 1 : c0 + r;
+                scan_points(bounds[row + za], bounds[row + zb + 1]);
+            } else {      // only the two end bins of the run are on the surface
+                if (c0 - r >= 0) {
+                    float g = gap(LVL, c0 - r, -r);
+                    if (!cannot_improve(partial + g * g)) scan_points(bounds[row + c0 - r], bounds[row + c0 - r + 1]);
+                }
+                if (c0 + r <= neff[LVL] - 1) {
+                    float g = gap(LVL, c0 + r, r);
+                    if (!cannot_improve(partial + g * g)) scan_points(bounds[row + c0 + r], bounds[row + c0 + r + 1]);
+                }
+            }
+        }
+    }
+
+    // after shell r: true when the search may stop
+    __device__ __forceinline__ bool certified(int32_t r) const
+    {
+        bool covered = true;
+        float mingap = 3.0e38f;
+#pragma unroll
+        for (int c = 0; c < DB; ++c) {
+            int32_t jl = cc[c] - r, jh = cc[c] + r;
+            if (jl > 0) {
+                covered = false;
+                float g = x[c] - (glo[c] + (float)jl * gw[c]) - gslack[c];
+                mingap = fminf(mingap, g > 0.0f ? g : 0.0f);
+            }
+            if (jh < neff[c] - 1) {
+                covered = false;
+                float g = (glo[c] + (float)(jh + 1) * gw[c]) - x[c] - gslack[c];
+                mingap = fminf(mingap, g > 0.0f ? g : 0.0f);
+            }
+        }
+        if (covered) return true;
+        return cannot_improve(mingap * mingap);
+    }
+
+    __device__ __forceinline__ void run()
+    {
+        if (cap <= 0) return;
+        for (int32_t r = 0;; ++r) {      // ends at the latest when the cube covers the grid (r = n_bins - 1)
+            visit<0>(r, 0, 0.0f, r == 0);
+            if (certified(r)) break;
+        }
+    }
+
+    // heap -> ascending order in place
+    __device__ __forceinline__ void sort_ascending()
+    {
+        for (int32_t m = filled - 1; m > 0; --m) {
+            uint64_t top = heap[0];
+            uint64_t last = heap[m * kQueryBlock];
+            heap[m * kQueryBlock] = top;
+            sift_down(last, m);
+        }
+    }
+};
+
+template <int D, int DB, bool COUNT>
+__global__ void __launch_bounds__(kQueryBlock)
+k_query_shell(QueryArgs a)
+{
+    extern __shared__ uint64_t heap_lds[];
+    const int32_t p = blockIdx.x * kQueryBlock + threadIdx.x;
+    if (p >= a.n) return;
+
+    ShellSearch<D, DB, COUNT> s;
+    s.heap = heap_lds + threadIdx.x;
+    s.soa = a.soa; s.perm = a.perm; s.bounds = a.bounds; s.stride = a.soa_stride;
+    s.n_bins = a.n_bins; s.self_pos = p; s.cap = a.k - 1; s.filled = 0; s.cand = 0;
+    s.tau = ~0ull;
+    const int32_t seg = segment_of(a.row_splits, a.n_segments, p);
+    s.seg_cell0 = seg * a.cells_per_segment;
+#pragma unroll
+    for (int c = 0; c < D; ++c) s.x[c] = a.soa[(int64_t)c * a.soa_stride + p];
+    const float* g = a.geom + (int64_t)seg * DB * kGeomStride;
+#pragma unroll
+    for (int c = 0; c < DB; ++c) {
+        float inv_w = g[c * kGeomStride + 1];
+        s.glo[c] = g[c * kGeomStride + 0];
+        s.gw[c] = g[c * kGeomStride + 2];
+        s.gslack[c] = g[c * kGeomStride + 3];
+        s.cc[c] = cell_of(s.x[c], s.glo[c], inv_w, a.n_bins);
+        s.neff[c] = inv_w > 0.0f ? a.n_bins : 1;
+    }
+
+    s.run();
+    s.sort_ascending();
+
+    const int32_t row = a.perm[p];
+    int32_t* oi = a.out_idx + (int64_t)row * a.k;
+    float* od = a.out_d2 + (int64_t)row * a.k;
+    oi[0] = row;
+    od[0] = 0.0f;
+    for (int32_t j = 0; j < s.cap; ++j) {
+        if (j < s.filled) {
+            uint64_t key = s.heap[j * kQueryBlock];
+            oi[j + 1] = (int32_t)(uint32_t)key;
+            od[j + 1] = __uint_as_float((uint32_t)(key >> 32));
+        } else {
+            oi[j + 1] = -1;
+            od[j + 1] = 0.0f;
+        }
+    }
+    if (COUNT) a.out_cand[row] = s.cand;
+}
+
+template <int D, int DB>
+static hipError_t launch_query_shell(const QueryArgs& a, hipStream_t stream)
+{
+    const int grid = (a.n + kQueryBlock - 1) / kQueryBlock;
+    const size_t lds = (size_t)(a.k > 1 ? a.k - 1 : 1) * kQueryBlock * sizeof(uint64_t);
+    if (a.out_cand)
+        hipLaunchKernelGGL((k_query_shell<D, DB, true>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
+    else
+        hipLaunchKernelGGL((k_query_shell<D, DB, false>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
+    return hipGetLastError();
+}
+
+template <int D>
+static hipError_t dispatch_query_dbin(const QueryArgs& a, int32_t d_bin, hipStream_t stream)
+{
+    switch (d_bin) {
+        case 2: return launch_query_shell<D, 2>(a, stream);
+        case 3: if constexpr (D >= 3) return launch_query_shell<D, 3>(a, stream); break;
+        case 4: if constexpr (D >= 4) return launch_query_shell<D, 4>(a, stream); break;
+        case 5: if constexpr (D >= 5) return launch_query_shell<D, 5>(a, stream); break;
+        default: break;
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace fg
