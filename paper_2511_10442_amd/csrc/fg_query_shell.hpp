@@ -35,6 +35,9 @@ struct ShellSearch {
     int64_t stride;
     int32_t n_bins, seg_cell0, self_pos, cap, filled, cand;
     uint64_t tau;     // worst key kept so far once the heap is full, all-ones before
+#ifdef FG_DEBUG_SHELLS
+    int32_t last_r = 0;
+#endif
 
     __device__ __forceinline__ float tau_d2() const { return __uint_as_float((uint32_t)(tau >> 32)); }
 
@@ -172,7 +175,12 @@ struct ShellSearch {
         if (cap <= 0) return;
         for (int32_t r = 0;; ++r) {      // ends at the latest when the cube covers the grid (r = n_bins - 1)
             visit<0>(r, 0, 0.0f, r == 0);
-            if (certified(r)) break;
+            if (certified(r)) {
+#ifdef FG_DEBUG_SHELLS
+                last_r = r;
+#endif
+                break;
+            }
         }
     }
 
@@ -234,7 +242,11 @@ k_query_shell(QueryArgs a)
             od[j + 1] = 0.0f;
         }
     }
+#ifdef FG_DEBUG_SHELLS
+    if (COUNT) a.out_cand[row] = s.cand | (s.last_r << 24);
+#else
     if (COUNT) a.out_cand[row] = s.cand;
+#endif
 }
 
 template <int D, int DB>
