@@ -65,7 +65,7 @@ fg_status fg_auto_n_bins(int64_t n, int32_t n_segments, int32_t k, int32_t d, in
 
 /* Bytes of workspace needed by fg_bin_points / fg_binned_select_knn / fg_knn_backward for this
  * problem (n_bins <= 0 or d_bin <= 0: the values fg_auto_n_bins mode 1 would choose).
- * bytes: host out.  O(n * (d + 4) + n_segments * n_bins^d_bin) words ("virtually no memory
+ * bytes: host out.  O(n * (d + 5) + n_segments * n_bins^d_bin) words ("virtually no memory
  * overhead", Abstract). */
 fg_status fg_workspace_size(int64_t n, int32_t d, int32_t n_segments, int32_t k,
                             int32_t n_bins, int32_t d_bin, size_t* bytes);
@@ -83,6 +83,10 @@ typedef struct {
     int64_t cells_per_segment; /* T = n_bins^d_bin */
     int32_t n_bins;            /* bins per binning dimension actually used */
     int32_t d_bin;             /* binning dimensions actually used (the first d_bin coordinates) */
+    int32_t* work_list;        /* [n]  scratch of the query stage: queries handed from the tile kernel to the list kernel */
+    int32_t* work_count;       /* [1]  scratch of the query stage */
+    int32_t query_algo;        /* 0 (set by fg_bin_points): tile kernel + list kernel; 1: the one-lane-per-query
+                                  shell walk for every query (slower; same result; kept for cross-checking) */
 } fg_binning;
 
 /* Spatial partition + counting sort (Section 3: "points are sorted by bin assignments and

@@ -38,7 +38,8 @@ class _Binning(ctypes.Structure):
                 ("bin_bounds", ctypes.c_void_p), ("sorted_soa", ctypes.c_void_p),
                 ("seg_geom", ctypes.c_void_p), ("soa_stride", ctypes.c_int64),
                 ("cells_per_segment", ctypes.c_int64), ("n_bins", ctypes.c_int32),
-                ("d_bin", ctypes.c_int32)]
+                ("d_bin", ctypes.c_int32), ("work_list", ctypes.c_void_p),
+                ("work_count", ctypes.c_void_p), ("query_algo", ctypes.c_int32)]
 
 
 _lib = None
@@ -156,6 +157,11 @@ class Binning:
     @property
     def sorted_soa(self):
         return self._view(self.raw.sorted_soa, self.d * self.soa_stride, torch.float32).view(self.d, self.soa_stride)
+
+    @property
+    def work_count(self):
+        """Number of queries the tile kernel handed to the list kernel in the last query call."""
+        return self._view(self.raw.work_count, 1, torch.int32)
 
     @property
     def seg_geom(self):

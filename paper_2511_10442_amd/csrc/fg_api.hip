@@ -44,7 +44,7 @@ constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t keys, geom, bin_idx, rank, perm, soa, bounds, partials, total;
+    size_t keys, geom, bin_idx, rank, perm, soa, bounds, partials, work_list, work_count, total;
     int64_t soa_stride, total_bins, cells_per_segment;
 };
 
@@ -66,6 +66,8 @@ Layout make_layout(int64_t n, int32_t d, int32_t n_segments, int32_t n_bins, int
     L.soa = off;      off = align_up(off + sizeof(float) * (size_t)L.soa_stride * d);
     L.bounds = off;   off = align_up(off + sizeof(int32_t) * (size_t)(L.total_bins + 1));
     L.partials = off; off = align_up(off + sizeof(int32_t) * (size_t)((L.total_bins + 1 + kScanChunkHost - 1) / kScanChunkHost));
+    L.work_list = off; off = align_up(off + sizeof(int32_t) * (size_t)n);
+    L.work_count = off; off = align_up(off + sizeof(int32_t));
     L.total = off;
     return L;
 }
@@ -189,6 +191,9 @@ fg_status fg_bin_points(const float* coords, const int32_t* row_splits, int64_t 
     view->cells_per_segment = L.cells_per_segment;
     view->n_bins = n_bins;
     view->d_bin = d_bin;
+    view->work_list = (int32_t*)(ws + L.work_list);
+    view->work_count = (int32_t*)(ws + L.work_count);
+    view->query_algo = 0;
     if (n == 0) return FG_OK;
     hipError_t e = launch_binning(coords, row_splits, (int32_t)n, d, n_segments, n_bins, d_bin, L.total_bins,
                                   (uint32_t*)(ws + L.keys), (float*)(ws + L.geom), (int32_t*)(ws + L.bin_idx),
@@ -207,7 +212,7 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
     if (st != FG_OK) return st;
     if (n == 0) return FG_OK;
     if (!row_splits || !out_idx || !out_d2 || !view->perm || !view->bin_bounds || !view->sorted_soa ||
-        !view->seg_geom)
+        !view->seg_geom || !view->work_list || !view->work_count)
         return FG_ERR_NULL;
     if (view->d_bin < FG_MIN_D_BIN || view->d_bin > FG_MAX_D_BIN || view->d_bin > d) return FG_ERR_UNSUPPORTED;
     if (view->n_bins < 1 || view->cells_per_segment < 1 ||
@@ -218,6 +223,7 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
     a.row_splits = row_splits; a.out_idx = out_idx; a.out_d2 = out_d2; a.out_cand = out_candidates;
     a.soa_stride = view->soa_stride; a.n = (int32_t)n; a.n_segments = n_segments; a.k = k;
     a.n_bins = view->n_bins; a.cells_per_segment = (int32_t)view->cells_per_segment;
+    a.work_list = view->work_list; a.work_count = view->work_count; a.algo = view->query_algo == 1 ? 1 : 0;
     hipError_t e = launch_query(a, d, view->d_bin, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }

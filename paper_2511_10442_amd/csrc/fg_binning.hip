@@ -49,35 +49,78 @@ __device__ __forceinline__ float wave_max(float v)
     return v;
 }
 
-// One point per thread.  A wave whose lanes all sit in one row split reduces in registers and
-// issues one atomic pair per dimension; a wave straddling a split boundary falls back to
-// per-lane atomics.
+// One block per chunk of kBboxChunk consecutive points.  A chunk that lies inside one row split
+// (the common case) is reduced in registers, then across the wave, then across the block, and
+// issues one atomic pair per dimension; a chunk straddling a split boundary falls back to
+// per-wave or per-lane atomics.  Same-address atomics serialise, so their number matters.
+constexpr int kBboxItems = 16;
+constexpr int kBboxChunk = kBlock * kBboxItems;
+
 template <int DB>
 __global__ void __launch_bounds__(kBlock)
 k_bbox(const float* __restrict__ coords, const int32_t* __restrict__ row_splits, int32_t n, int32_t d,
        int32_t n_segments, uint32_t* __restrict__ bbox_keys)
 {
-    int32_t i = blockIdx.x * kBlock + threadIdx.x;
-    bool live = i < n;
-    int32_t ii = live ? i : n - 1;
-    int32_t s = segment_of(row_splits, n_segments, ii);
-    int32_t s0 = __shfl(s, 0, 64);
-    bool uniform = __all(s == s0);
+    __shared__ float red[2][kBlock / 64][DB];
+    const int64_t base = (int64_t)blockIdx.x * kBboxChunk;
+    const int32_t last = (int32_t)(base + kBboxChunk < n ? base + kBboxChunk : n) - 1;
     uint32_t* kmin = bbox_keys;
     uint32_t* kmax = bbox_keys + (int64_t)n_segments * DB;
-    const float* p = coords + (int64_t)ii * d;
+    const int32_t s_first = segment_of(row_splits, n_segments, (int32_t)base);
+    const int32_t s_last = segment_of(row_splits, n_segments, last);
+    if (s_first == s_last) {
+        float mn[DB], mx[DB];
 #pragma unroll
-    for (int c = 0; c < DB; ++c) {
-        float x = p[c];
-        if (uniform) {
-            float mn = wave_min(x), mx = wave_max(x);   // dead lanes duplicate point n-1: harmless
-            if ((threadIdx.x & 63) == 0) {
-                atomicMin(&kmin[s * DB + c], float_to_key(mn));
-                atomicMax(&kmax[s * DB + c], float_to_key(mx));
+        for (int c = 0; c < DB; ++c) { mn[c] = 3.4028235e38f; mx[c] = -3.4028235e38f; }
+        for (int it = 0; it < kBboxItems; ++it) {
+            const int64_t i = base + it * kBlock + threadIdx.x;
+            if (i <= last) {
+#pragma unroll
+                for (int c = 0; c < DB; ++c) {
+                    const float x = coords[i * d + c];
+                    mn[c] = fminf(mn[c], x);
+                    mx[c] = fmaxf(mx[c], x);
+                }
             }
-        } else if (live) {
-            atomicMin(&kmin[s * DB + c], float_to_key(x));
-            atomicMax(&kmax[s * DB + c], float_to_key(x));
+        }
+        const int wv = threadIdx.x >> 6;
+#pragma unroll
+        for (int c = 0; c < DB; ++c) {
+            const float a = wave_min(mn[c]), b = wave_max(mx[c]);
+            if ((threadIdx.x & 63) == 0) { red[0][wv][c] = a; red[1][wv][c] = b; }
+        }
+        __syncthreads();
+        if (threadIdx.x < DB) {
+            const int c = threadIdx.x;
+            float a = red[0][0][c], b = red[1][0][c];
+#pragma unroll
+            for (int w = 1; w < kBlock / 64; ++w) { a = fminf(a, red[0][w][c]); b = fmaxf(b, red[1][w][c]); }
+            atomicMin(&kmin[s_first * DB + c], float_to_key(a));
+            atomicMax(&kmax[s_first * DB + c], float_to_key(b));
+        }
+        return;
+    }
+    for (int it = 0; it < kBboxItems; ++it) {
+        const int64_t i = base + it * kBlock + threadIdx.x;
+        const bool live = i <= last;
+        const int32_t ii = live ? (int32_t)i : last;
+        const int32_t s = segment_of(row_splits, n_segments, ii);
+        const int32_t s0 = __shfl(s, 0, 64);
+        const bool uniform = __all(s == s0);
+        const float* p = coords + (int64_t)ii * d;
+#pragma unroll
+        for (int c = 0; c < DB; ++c) {
+            const float x = p[c];
+            if (uniform) {
+                const float a = wave_min(x), b = wave_max(x);   // dead lanes duplicate the chunk's last point: harmless
+                if ((threadIdx.x & 63) == 0) {
+                    atomicMin(&kmin[s * DB + c], float_to_key(a));
+                    atomicMax(&kmax[s * DB + c], float_to_key(b));
+                }
+            } else if (live) {
+                atomicMin(&kmin[s * DB + c], float_to_key(x));
+                atomicMax(&kmax[s * DB + c], float_to_key(x));
+            }
         }
     }
 }
@@ -235,8 +278,8 @@ static void launch_bbox_assign(bool assign, const float* coords, const int32_t* 
 {
     int grid = (n + kBlock - 1) / kBlock;
     if (!assign)
-        hipLaunchKernelGGL(k_bbox<DB>, dim3(grid), dim3(kBlock), 0, stream, coords, row_splits, n, d, n_segments,
-                           bbox_keys);
+        hipLaunchKernelGGL(k_bbox<DB>, dim3((n + kBboxChunk - 1) / kBboxChunk), dim3(kBlock), 0, stream, coords,
+                           row_splits, n, d, n_segments, bbox_keys);
     else
         hipLaunchKernelGGL(k_assign<DB>, dim3(grid), dim3(kBlock), 0, stream, coords, row_splits, n, d, n_segments,
                            n_bins, cells_per_segment, geom, bin_idx, rank, counters);

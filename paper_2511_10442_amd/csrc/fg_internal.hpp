@@ -18,12 +18,15 @@ struct QueryArgs {
     int32_t* out_idx;          // [n][k]
     float* out_d2;             // [n][k]
     int32_t* out_cand;         // [n] or nullptr
+    int32_t* work_list;        // [n] sorted positions of queries deferred by the tile kernel
+    int32_t* work_count;       // [1]
     int64_t soa_stride;
     int32_t n;
     int32_t n_segments;
     int32_t k;
     int32_t n_bins;
     int32_t cells_per_segment;
+    int32_t algo;              // 0: tile kernel + list kernel, 1: one lane per query for everything
 };
 
 // Host-side launchers, one per translation unit.  Each returns hipGetLastError() of its launches.

@@ -1,0 +1,449 @@
+// General shell-expanding exact query kernel: one lane per query, any shell radius.
+//
+// What it computes (paper Section 3, Algorithm 2): for every point, the K-1 nearest other
+// points of its row split, found by scanning the bins on the surface of the hypercube of
+// Chebyshev radius r = 0, 1, 2, ... around the query's bin (Algorithm 1) until the k-th best
+// squared distance is certified smaller than anything unsearched.  Differences from the
+// paper's kernel, none of which changes what "exact" means:
+//   * the running best list is a max-heap of 64-bit keys (distance bits << 32 | original index)
+//     in LDS, one column per lane, instead of an unsorted buffer with a linear max rescan; the
+//     key order is the strict total order (d2, index), so the result does not depend on the
+//     order candidates arrive in;
+//   * the last binning dimension is walked as contiguous runs of bins (bins adjacent in the
+//     last dimension are adjacent in the sorted point order);
+//   * bins whose box lies farther than the current k-th best are skipped (a lower bound on the
+//     distance to any point of the bin, per dimension, with rounding slack);
+//   * the stop test uses the true distance from the query to the faces of the searched cube
+//     instead of r times the first bin width, and stops at once when the cube covers the grid.
+#pragma once
+#include "fg_internal.hpp"
+
+namespace fg {
+
+constexpr int kQueryBlock = 64;                    // one wavefront per workgroup
+constexpr int kStageChunk = 256;                  // points staged through LDS per chunk (tile kernel)
+constexpr float kBoundShrink = 0.99999618530273f;  // 1 - 2^-18: covers fp32 rounding of d2 and of the bound
+
+// Per-lane geometry of one query: its coordinates, its bin, its row split's grid, and the
+// current k-th best key `tau` (all-ones until K-1 candidates have been kept).
+template <int D, int DB>
+struct LaneGeom {
+    float x[D];
+    float glo[DB], gw[DB], gslack[DB];
+    int32_t cc[DB], neff[DB];
+    int32_t n_bins, seg_cell0;
+    uint64_t tau;
+
+    __device__ __forceinline__ float tau_d2() const { return __uint_as_float((uint32_t)(tau >> 32)); }
+
+    // true when no point of a box at squared lower-bound distance b2 can enter the best list
+    __device__ __forceinline__ bool cannot_improve(float b2) const
+    {
+        return tau != ~0ull && b2 > 1e-30f && tau_d2() < b2 * kBoundShrink;
+    }
+
+    // lower bound (>= 0) on |x_c - y_c| for any point y whose bin index in dimension c is j = cc[c] + o
+    __device__ __forceinline__ float gap(int c, int32_t j, int32_t o) const
+    {
+        if (o == 0) return 0.0f;
+        float g = (o > 0) ? (glo[c] + (float)j * gw[c]) - x[c] : x[c] - (glo[c] + (float)(j + 1) * gw[c]);
+        g -= gslack[c];
+        return g > 0.0f ? g : 0.0f;
+    }
+
+    // after shell r: true when the search may stop
+    __device__ __forceinline__ bool certified(int32_t r) const
+    {
+        bool covered = true;
+        float mingap = 3.0e38f;
+#pragma unroll
+        for (int c = 0; c < DB; ++c) {
+            int32_t jl = cc[c] - r, jh = cc[c] + r;
+            if (jl > 0) {
+                covered = false;
+                float g = x[c] - (glo[c] + (float)jl * gw[c]) - gslack[c];
+                mingap = fminf(mingap, g > 0.0f ? g : 0.0f);
+            }
+            if (jh < neff[c] - 1) {
+                covered = false;
+                float g = (glo[c] + (float)(jh + 1) * gw[c]) - x[c] - gslack[c];
+                mingap = fminf(mingap, g > 0.0f ? g : 0.0f);
+            }
+        }
+        if (covered) return true;
+        return cannot_improve(mingap * mingap);
+    }
+
+    // p: sorted position of the query
+    __device__ __forceinline__ void init_geom(const QueryArgs& a, int32_t p)
+    {
+        n_bins = a.n_bins;
+        tau = ~0ull;
+        const int32_t seg = segment_of(a.row_splits, a.n_segments, p);
+        seg_cell0 = seg * a.cells_per_segment;
+#pragma unroll
+        for (int c = 0; c < D; ++c) x[c] = a.soa[(int64_t)c * a.soa_stride + p];
+        const float* g = a.geom + (int64_t)seg * DB * kGeomStride;
+#pragma unroll
+        for (int c = 0; c < DB; ++c) {
+            const float inv_w = g[c * kGeomStride + 1];
+            glo[c] = g[c * kGeomStride + 0];
+            gw[c] = g[c * kGeomStride + 2];
+            gslack[c] = g[c * kGeomStride + 3];
+            cc[c] = cell_of(x[c], glo[c], inv_w, a.n_bins);
+            neff[c] = inv_w > 0.0f ? a.n_bins : 1;
+        }
+    }
+};
+
+template <int D, int DB, bool COUNT>
+struct ShellSearch : LaneGeom<D, DB> {
+    using G = LaneGeom<D, DB>;
+    using G::x; using G::glo; using G::gw; using G::gslack; using G::cc; using G::neff;
+    using G::n_bins; using G::seg_cell0; using G::tau;
+    using G::cannot_improve; using G::gap; using G::certified;
+    uint64_t* heap;   // this lane's column: slot j lives at heap[j * kQueryBlock]
+    const float* __restrict__ soa;
+    const int32_t* __restrict__ perm;
+    const int32_t* __restrict__ bounds;
+    int64_t stride;
+    int32_t self_pos, cap, filled, cand;
+#ifdef FG_DEBUG_SHELLS
+    int32_t last_r = 0;
+#endif
+
+    __device__ __forceinline__ void sift_down(uint64_t key, int32_t size)
+    {
+        int32_t i = 0;
+        for (;;) {
+            int32_t l = 2 * i + 1;
+            if (l >= size) break;
+            uint64_t bk = heap[l * kQueryBlock];
+            int32_t big = l;
+            if (l + 1 < size) {
+                uint64_t rk = heap[(l + 1) * kQueryBlock];
+                if (rk > bk) { bk = rk; big = l + 1; }
+            }
+            if (bk <= key) break;
+            heap[i * kQueryBlock] = bk;
+            i = big;
+        }
+        heap[i * kQueryBlock] = key;
+    }
+
+    __device__ __forceinline__ void offer(uint64_t key)
+    {
+        if (filled < cap) {
+            int32_t i = filled++;
+            while (i > 0) {
+                int32_t parent = (i - 1) >> 1;
+                uint64_t pk = heap[parent * kQueryBlock];
+                if (pk >= key) break;
+                heap[i * kQueryBlock] = pk;
+                i = parent;
+            }
+            heap[i * kQueryBlock] = key;
+            if (filled == cap) tau = heap[0];
+        } else if (key < tau) {
+            sift_down(key, cap);
+            tau = heap[0];
+        }
+    }
+
+    // all points at sorted positions [a, b)
+    __device__ __forceinline__ void scan_points(int32_t a, int32_t b)
+    {
+        for (int32_t q = a; q < b; ++q) {
+            if (q == self_pos) continue;
+            float diff = x[0] - soa[q];
+            float d2 = diff * diff;
+#pragma unroll
+            for (int c = 1; c < D; ++c) {
+                diff = x[c] - soa[(int64_t)c * stride + q];
+                d2 = d2 + diff * diff;
+            }
+            if (COUNT) ++cand;
+            uint32_t bits = __float_as_uint(d2);
+            if (bits > (uint32_t)(tau >> 32)) continue;
+            uint64_t key = ((uint64_t)bits << 32) | (uint32_t)perm[q];
+            offer(key);
+        }
+    }
+
+    // staged points: LDS holds sorted positions [base, base+cnt); scan the part of [lo, hi) inside it
+    __device__ __forceinline__ void scan_staged(const float* stage, const int32_t* stage_idx, int32_t base,
+                                                int32_t cnt, int32_t lo, int32_t hi)
+    {
+        lo = lo > base ? lo : base;
+        hi = hi < base + cnt ? hi : base + cnt;
+        for (int32_t q = lo; q < hi; ++q) {
+            if (q == self_pos) continue;
+            const int32_t i = q - base;
+            float diff = x[0] - stage[i];
+            float d2 = diff * diff;
+#pragma unroll
+            for (int c = 1; c < D; ++c) {
+                diff = x[c] - stage[c * kStageChunk + i];
+                d2 = d2 + diff * diff;
+            }
+            if (COUNT) ++cand;
+            uint32_t bits = __float_as_uint(d2);
+            if (bits > (uint32_t)(tau >> 32)) continue;
+            offer(((uint64_t)bits << 32) | (uint32_t)stage_idx[i]);
+        }
+    }
+
+    template <int LVL>
+    __device__ __forceinline__ void visit(int32_t r, int32_t flat, float partial, bool surf)
+    {
+        const int32_t c0 = cc[LVL];
+        if constexpr (LVL < DB - 1) {
+            int32_t o_lo = -r < -c0 ? -c0 : -r;
+            int32_t o_hi = r > neff[LVL] - 1 - c0 ? neff[LVL] - 1 - c0 : r;
+            for (int32_t o = o_lo; o <= o_hi; ++o) {
+                float g = gap(LVL, c0 + o, o);
+                float p2 = partial + g * g;
+                if (cannot_improve(p2)) continue;
+                bool on = surf || o == r || o == -r;
+                visit<LVL + 1>(r, flat * n_bins + c0 + o, p2, on);
+            }
+        } else {
+            const int32_t row = seg_cell0 + flat * n_bins;
+            if (surf) {   // the whole run of the last dimension belongs to this shell
+                int32_t za = c0 - r < 0 ? 0 : c0 - r;
+                int32_t zb = c0 + r > neff[LVL] - 1 ? neff[LVL] - 1 : c0 + r;
+                scan_points(bounds[row + za], bounds[row + zb + 1]);
+            } else {      // only the two end bins of the run are on the surface
+                if (c0 - r >= 0) {
+                    float g = gap(LVL, c0 - r, -r);
+                    if (!cannot_improve(partial + g * g)) scan_points(bounds[row + c0 - r], bounds[row + c0 - r + 1]);
+                }
+                if (c0 + r <= neff[LVL] - 1) {
+                    float g = gap(LVL, c0 + r, r);
+                    if (!cannot_improve(partial + g * g)) scan_points(bounds[row + c0 + r], bounds[row + c0 + r + 1]);
+                }
+            }
+        }
+    }
+
+    __device__ __forceinline__ void run()
+    {
+        if (cap <= 0) return;
+        for (int32_t r = 0;; ++r) {      // ends at the latest when the cube covers the grid (r = n_bins - 1)
+            visit<0>(r, 0, 0.0f, r == 0);
+            if (certified(r)) {
+#ifdef FG_DEBUG_SHELLS
+                last_r = r;
+#endif
+                break;
+            }
+        }
+    }
+
+    // heap -> ascending order in place
+    __device__ __forceinline__ void sort_ascending()
+    {
+        for (int32_t m = filled - 1; m > 0; --m) {
+            uint64_t top = heap[0];
+            uint64_t last = heap[m * kQueryBlock];
+            heap[m * kQueryBlock] = top;
+            sift_down(last, m);
+        }
+    }
+};
+
+// ---- per-lane set-up and output, shared by both kernels ------------------------------------
+
+template <int D, int DB, bool COUNT>
+__device__ __forceinline__ void init_lane(ShellSearch<D, DB, COUNT>& s, const QueryArgs& a, int32_t p, uint64_t* heap)
+{
+    s.heap = heap;
+    s.soa = a.soa; s.perm = a.perm; s.bounds = a.bounds; s.stride = a.soa_stride;
+    s.self_pos = p; s.cap = a.k - 1; s.filled = 0; s.cand = 0;
+    s.init_geom(a, p);
+}
+
+// sort the lane's best list and write its output row (original row order)
+template <int D, int DB, bool COUNT>
+__device__ __forceinline__ void write_row(ShellSearch<D, DB, COUNT>& s, const QueryArgs& a, int32_t p, bool add_count)
+{
+    s.sort_ascending();
+    const int32_t row = a.perm[p];
+    int32_t* oi = a.out_idx + (int64_t)row * a.k;
+    float* od = a.out_d2 + (int64_t)row * a.k;
+    oi[0] = row;
+    od[0] = 0.0f;
+    for (int32_t j = 0; j < s.cap; ++j) {
+        if (j < s.filled) {
+            uint64_t key = s.heap[j * kQueryBlock];
+            oi[j + 1] = (int32_t)(uint32_t)key;
+            od[j + 1] = __uint_as_float((uint32_t)(key >> 32));
+        } else {
+            oi[j + 1] = -1;
+            od[j + 1] = 0.0f;
+        }
+    }
+#ifndef FG_TILE_PROF
+    if (COUNT) a.out_cand[row] = (add_count ? a.out_cand[row] : 0) + s.cand;
+#endif
+}
+
+// ---- main pass: one wavefront per tile of 64 consecutive bin-ordered queries ----------------
+//
+// The shell walk of Algorithm 2 is made wave-uniform: all 64 lanes step through the same
+// column offsets (offsets in the first DB-1 binning dimensions) of the same shell at the same
+// time.  Because the queries of a tile are consecutive in bin order, the bins they need for one
+// column offset form one contiguous range of sorted points; that range is staged through LDS
+// in chunks with coalesced loads and every lane scans only its own sub-range of the chunk.
+// Lanes certify independently after every shell.  When few lanes are left the wave stops and
+// hands them to the list kernel below, so that a handful of far-searching queries (isolated
+// points) does not keep 64 lanes busy.
+
+constexpr int kDeferLanes = 48;    // after shell 1, go on to the next shell only while more lanes than this are unfinished
+
+__device__ __forceinline__ int32_t wave_min_i32(int32_t v)
+{
+    for (int o = 32; o > 0; o >>= 1) { int32_t t = __shfl_xor(v, o, 64); v = t < v ? t : v; }
+    return v;
+}
+__device__ __forceinline__ int32_t wave_max_i32(int32_t v)
+{
+    for (int o = 32; o > 0; o >>= 1) { int32_t t = __shfl_xor(v, o, 64); v = t > v ? t : v; }
+    return v;
+}
+
+template <int D, int DB, bool COUNT>
+__global__ void __launch_bounds__(kQueryBlock)
+k_query_tile(QueryArgs a)
+{
+    extern __shared__ uint64_t lds64[];
+    const int lane = threadIdx.x;
+    const int32_t cap = a.k - 1;
+    float* stage = reinterpret_cast<float*>(lds64 + (size_t)(cap > 0 ? cap : 0) * kQueryBlock);
+    int32_t* stage_idx = reinterpret_cast<int32_t*>(stage + D * kStageChunk);
+
+    const int32_t p = blockIdx.x * kQueryBlock + lane;
+    const bool valid = p < a.n;
+    ShellSearch<D, DB, COUNT> s;
+    init_lane(s, a, valid ? p : a.n - 1, lds64 + lane);   // dead lanes shadow the last point, never scan or write
+    s.self_pos = p;
+    bool active = valid && cap > 0;
+
+    for (int32_t R = 0;; ++R) {   // ends at the latest at R = n_bins - 1, when every lane's cube covers its grid
+        const int32_t side = 2 * R + 1;
+        int32_t ncols = 1;
+#pragma unroll
+        for (int c = 0; c < DB - 1; ++c) ncols *= side;
+        for (int32_t t = 0; t < ncols; ++t) {
+            // column offsets, wave-uniform; digit v of t maps to 0, +1, -1, +2, -2, ... (centre first)
+            int32_t o[DB - 1];
+            bool surf = false;
+            {
+                int32_t rem = t;
+#pragma unroll
+                for (int c = DB - 2; c >= 0; --c) {
+                    int32_t v = rem % side;
+                    rem /= side;
+                    o[c] = (v & 1) ? ((v + 1) >> 1) : -(v >> 1);
+                    surf = surf || o[c] == R || o[c] == -R;
+                }
+            }
+            bool ok = active;
+            float partial = 0.0f;
+            int32_t flat = 0;
+#pragma unroll
+            for (int c = 0; c < DB - 1; ++c) {
+                const int32_t j = s.cc[c] + o[c];
+                ok = ok && j >= 0 && j < s.neff[c];
+                const float g = s.gap(c, j, o[c]);
+                partial += g * g;
+                flat = flat * a.n_bins + j;
+            }
+            ok = ok && !s.cannot_improve(partial);
+            int32_t a1 = 0, b1 = 0, a2 = 0, b2 = 0;
+            if (ok) {
+                const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
+                const int32_t row = s.seg_cell0 + flat * a.n_bins;
+                if (surf) {
+                    const int32_t za = cz - R < 0 ? 0 : cz - R;
+                    const int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
+                    a1 = a.bounds[row + za];
+                    b1 = a.bounds[row + zb + 1];
+                } else {
+                    if (cz - R >= 0) {
+                        const float g = s.gap(DB - 1, cz - R, -R);
+                        if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[row + cz - R]; b1 = a.bounds[row + cz - R + 1]; }
+                    }
+                    if (cz + R <= nz - 1) {
+                        const float g = s.gap(DB - 1, cz + R, R);
+                        if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[row + cz + R]; b2 = a.bounds[row + cz + R + 1]; }
+                    }
+                }
+            }
+            int32_t lo = 0x7fffffff, hi = 0;
+            if (b1 > a1) { lo = a1; hi = b1; }
+            if (b2 > a2) { lo = a2 < lo ? a2 : lo; hi = b2 > hi ? b2 : hi; }
+            const int32_t PA = wave_min_i32(lo), PB = wave_max_i32(hi);
+            for (int32_t base = PA; base < PB; base += kStageChunk) {
+                const int32_t cnt = PB - base < kStageChunk ? PB - base : kStageChunk;
+                __syncthreads();
+                for (int32_t i = lane; i < cnt; i += kQueryBlock) {
+#pragma unroll
+                    for (int c = 0; c < D; ++c) stage[c * kStageChunk + i] = a.soa[(int64_t)c * a.soa_stride + base + i];
+                    stage_idx[i] = a.perm[base + i];
+                }
+                __syncthreads();
+                s.scan_staged(stage, stage_idx, base, cnt, a1, b1);
+                s.scan_staged(stage, stage_idx, base, cnt, a2, b2);
+            }
+        }
+        if (active && s.certified(R)) active = false;
+        const int32_t n_active = __popcll(__ballot(active));
+        if (n_active == 0) break;
+        if (R >= 1 && n_active <= kDeferLanes) break;
+    }
+
+    // unfinished lanes go to the work list (wave-aggregated append); the rest write their rows
+    const uint64_t mask = __ballot(active);
+    if (mask) {
+        int32_t base = 0;
+        const int leader = __ffsll((unsigned long long)mask) - 1;
+        if (lane == leader) base = atomicAdd(a.work_count, __popcll(mask));
+        base = __shfl(base, leader, 64);
+        if (active) a.work_list[base + __popcll(mask & ((1ull << lane) - 1))] = p;
+    }
+    if (valid && !active) write_row(s, a, p, false);
+    else if (COUNT && valid) a.out_cand[a.perm[p]] = s.cand;   // work done here counts too
+}
+
+// ---- list pass: the general one-lane-per-query shell walk over the deferred queries ---------
+template <int D, int DB, bool COUNT>
+__global__ void __launch_bounds__(kQueryBlock)
+k_query_list(QueryArgs a)
+{
+    extern __shared__ uint64_t lds64[];
+    const int32_t count = *a.work_count;
+    for (int32_t i = blockIdx.x * kQueryBlock + threadIdx.x; i < count; i += gridDim.x * kQueryBlock) {
+        const int32_t p = a.work_list[i];
+        ShellSearch<D, DB, COUNT> s;
+        init_lane(s, a, p, lds64 + threadIdx.x);
+        s.run();
+        write_row(s, a, p, true);
+    }
+}
+
+// all queries through the one-lane-per-query walk (no tiles, no work list)
+template <int D, int DB, bool COUNT>
+__global__ void __launch_bounds__(kQueryBlock)
+k_query_shell(QueryArgs a)
+{
+    extern __shared__ uint64_t lds64[];
+    const int32_t p = blockIdx.x * kQueryBlock + threadIdx.x;
+    if (p >= a.n) return;
+    ShellSearch<D, DB, COUNT> s;
+    init_lane(s, a, p, lds64 + threadIdx.x);
+    s.run();
+    write_row(s, a, p, false);
+}
+
+}  // namespace fg

@@ -1,7 +1,7 @@
 // One translation unit per coordinate count: compile with -DFG_QUERY_D=<2..10>.
 // (Compile-time specialisation per dimension, as in the paper's Section 3: loops over
 // coordinates and binning dimensions unroll and per-dimension state stays in registers.)
-#include "fg_query_shell.hpp"
+#include "fg_query_launch.hpp"
 
 #ifndef FG_QUERY_D
 #error "define FG_QUERY_D"

@@ -1,0 +1,207 @@
+// List kernel: the queries the tile kernel hands over (isolated points, sparse regions) are
+// searched ONE QUERY PER WAVEFRONT.
+//
+// Same algorithm as everywhere (paper Section 3, Algorithm 2: shells of growing radius, exact
+// best K-1, certified stop), but the parallelism is across the shell instead of across queries:
+//   * the column offsets of a shell (offsets in the first DB-1 binning dimensions) are spread
+//     over the lanes, 64 at a time: one round trip fetches the bin boundaries of 64 columns;
+//   * the candidates of those columns are flattened with a wave prefix sum and evaluated 64 per
+//     pass, one per lane, straight from the bin-ordered coordinates (runs of consecutive
+//     points, so the loads coalesce);
+//   * candidates that beat the current k-th best are compacted (ballot + popcount) into a
+//     pending array in LDS; 64 pending keys at a time are sorted across the lanes with a
+//     shuffle-based bitonic network and merged into the best list, which lives one key per lane,
+//     ascending by lane;
+//   * the output row is written by the lanes that hold it: one contiguous store per row.
+// A far-searching query therefore costs a few memory round trips per shell, not one per bin.
+// Used for K-1 <= 64; larger K falls back to the one-lane-per-query list kernel.
+#pragma once
+#include "fg_query.hpp"
+
+namespace fg {
+
+__device__ __forceinline__ uint64_t wave_sort_step(uint64_t v, int lane, int k, int j)
+{
+    const uint64_t other = __shfl_xor(v, j, 64);
+    const bool keep_min = ((lane & k) == 0) == ((lane & j) == 0);
+    const uint64_t mn = other < v ? other : v;
+    const uint64_t mx = other < v ? v : other;
+    return keep_min ? mn : mx;
+}
+
+// ascending (by lane) bitonic sort of one key per lane
+__device__ __forceinline__ uint64_t wave_sort64(uint64_t v, int lane)
+{
+#pragma unroll
+    for (int k = 2; k <= 64; k <<= 1)
+#pragma unroll
+        for (int j = k >> 1; j > 0; j >>= 1) v = wave_sort_step(v, lane, k, j);
+    return v;
+}
+
+// keys form a bitonic sequence over the lanes -> ascending
+__device__ __forceinline__ uint64_t wave_merge64(uint64_t v, int lane)
+{
+#pragma unroll
+    for (int j = 32; j > 0; j >>= 1) v = wave_sort_step(v, lane, 64, j);
+    return v;
+}
+
+__device__ __forceinline__ int32_t wave_incl_scan_i32(int32_t v, int lane)
+{
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int32_t t = __shfl_up(v, o, 64);
+        if (lane >= o) v += t;
+    }
+    return v;
+}
+
+constexpr int kListPend = 128;
+
+template <int D, int DB, bool COUNT>
+__global__ void __launch_bounds__(kQueryBlock)
+k_query_list_wave(QueryArgs a)
+{
+    __shared__ uint64_t pend[kListPend];
+    __shared__ int32_t seg_excl[kQueryBlock], seg_a1[kQueryBlock], seg_len1[kQueryBlock], seg_a2[kQueryBlock];
+    const int lane = threadIdx.x;
+    const int32_t count = *a.work_count;
+    const int32_t cap = a.k - 1;                    // 1 <= cap <= 64 here
+    const uint64_t lt_mask = (1ull << lane) - 1;
+
+    for (int32_t item = blockIdx.x; item < count; item += gridDim.x) {
+        const int32_t p = a.work_list[item];
+        LaneGeom<D, DB> s;                          // identical in every lane
+        s.init_geom(a, p);
+        uint64_t best = lane < kQueryBlock - cap ? 0ull : ~0ull;   // ascending by lane; low lanes pinned
+        int32_t npend = 0, cand = 0;
+
+        auto absorb64 = [&]() {                     // merges pend[0..min(npend,64)) into the best list
+            const int32_t take = npend < kQueryBlock ? npend : kQueryBlock;
+            uint64_t v = lane < take ? pend[lane] : ~0ull;
+            uint64_t rest = (lane + kQueryBlock < npend) ? pend[lane + kQueryBlock] : 0ull;
+            __syncthreads();
+            if (lane + kQueryBlock < npend) pend[lane] = rest;
+            npend -= take;
+            v = wave_sort64(v, lane);
+            const uint64_t rv = __shfl(v, kQueryBlock - 1 - lane, 64);
+            best = rv < best ? rv : best;
+            best = wave_merge64(best, lane);
+            s.tau = __shfl(best, kQueryBlock - 1, 64);
+            __syncthreads();
+        };
+
+        for (int32_t R = 0;; ++R) {   // ends at the latest when the cube covers the grid
+            const int32_t side = 2 * R + 1;
+            int32_t ncols = 1;
+#pragma unroll
+            for (int c = 0; c < DB - 1; ++c) ncols *= side;
+            for (int32_t t0 = 0; t0 < ncols; t0 += kQueryBlock) {
+                // this lane's column
+                const int32_t t = t0 + lane;
+                bool ok = t < ncols;
+                bool surf = false;
+                float partial = 0.0f;
+                int32_t flat = 0;
+                {
+                    int32_t o[DB - 1];
+                    int32_t rem = ok ? t : 0;
+#pragma unroll
+                    for (int c = DB - 2; c >= 0; --c) {
+                        const int32_t v = rem % side;
+                        rem /= side;
+                        o[c] = (v & 1) ? ((v + 1) >> 1) : -(v >> 1);
+                        surf = surf || o[c] == R || o[c] == -R;
+                    }
+#pragma unroll
+                    for (int c = 0; c < DB - 1; ++c) {
+                        const int32_t j = s.cc[c] + o[c];
+                        ok = ok && j >= 0 && j < s.neff[c];
+                        const float g = s.gap(c, j, o[c]);
+                        partial += g * g;
+                        flat = flat * a.n_bins + j;
+                    }
+                }
+                ok = ok && !s.cannot_improve(partial);
+                int32_t a1 = 0, b1 = 0, a2 = 0, b2 = 0;
+                if (ok) {
+                    const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
+                    const int32_t row = s.seg_cell0 + flat * a.n_bins;
+                    if (surf) {
+                        const int32_t za = cz - R < 0 ? 0 : cz - R;
+                        const int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
+                        a1 = a.bounds[row + za];
+                        b1 = a.bounds[row + zb + 1];
+                    } else {
+                        if (cz - R >= 0) {
+                            const float g = s.gap(DB - 1, cz - R, -R);
+                            if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[row + cz - R]; b1 = a.bounds[row + cz - R + 1]; }
+                        }
+                        if (cz + R <= nz - 1) {
+                            const float g = s.gap(DB - 1, cz + R, R);
+                            if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[row + cz + R]; b2 = a.bounds[row + cz + R + 1]; }
+                        }
+                    }
+                }
+                const int32_t len1 = b1 - a1, len = len1 + (b2 - a2);
+                const int32_t incl = wave_incl_scan_i32(len, lane);
+                const int32_t W = __shfl(incl, kQueryBlock - 1, 64);
+                __syncthreads();
+                seg_excl[lane] = incl - len; seg_a1[lane] = a1; seg_len1[lane] = len1; seg_a2[lane] = a2;
+                __syncthreads();
+                for (int32_t f0 = 0; f0 < W; f0 += kQueryBlock) {
+                    const int32_t f = f0 + lane;
+                    const bool in = f < W;
+                    // segment of candidate f: the largest j with seg_excl[j] <= f
+                    int32_t j = 0;
+#pragma unroll
+                    for (int step = 32; step > 0; step >>= 1)
+                        if (seg_excl[j + step] <= f) j += step;
+                    const int32_t local = f - seg_excl[j];
+                    const int32_t l1 = seg_len1[j];
+                    int32_t q = local < l1 ? seg_a1[j] + local : seg_a2[j] + (local - l1);
+                    q = in ? q : p;
+                    float diff = s.x[0] - a.soa[q];
+                    float d2 = diff * diff;
+#pragma unroll
+                    for (int c = 1; c < D; ++c) {
+                        diff = s.x[c] - a.soa[(int64_t)c * a.soa_stride + q];
+                        d2 = d2 + diff * diff;
+                    }
+                    const bool live = in && q != p;
+                    const uint64_t key = ((uint64_t)__float_as_uint(d2) << 32) | (uint32_t)a.perm[q];
+                    const bool acc = live && key < s.tau;
+                    if (COUNT) cand += __popcll(__ballot(live));
+                    const uint64_t m = __ballot(acc);
+                    if (m) {
+                        if (acc) pend[npend + __popcll(m & lt_mask)] = key;
+                        npend += __popcll(m);
+                        __syncthreads();
+                        if (npend > kQueryBlock) absorb64();
+                    }
+                }
+            }
+            while (npend > 0) absorb64();
+            if (s.certified(R)) break;
+        }
+
+        // output: slot 0 is the query itself, slot j >= 1 lives in lane 64 - cap + j - 1
+        const int32_t row = a.perm[p];
+        int32_t* oi = a.out_idx + (int64_t)row * a.k;
+        float* od = a.out_d2 + (int64_t)row * a.k;
+        if (lane == 0) { oi[0] = row; od[0] = 0.0f; }
+        if (lane >= kQueryBlock - cap) {
+            const int32_t j = lane - (kQueryBlock - cap) + 1;
+            const bool real = best != ~0ull;
+            oi[j] = real ? (int32_t)(uint32_t)best : -1;
+            od[j] = real ? __uint_as_float((uint32_t)(best >> 32)) : 0.0f;
+        }
+#ifndef FG_TILE_PROF
+        if (COUNT && lane == 0) a.out_cand[row] += cand;
+#endif
+        __syncthreads();
+    }
+}
+
+}  // namespace fg

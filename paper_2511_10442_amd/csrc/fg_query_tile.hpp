@@ -1,0 +1,281 @@
+// Main query kernel: one wavefront per tile of 64 consecutive bin-ordered queries, the running
+// best list of every lane held SORTED IN REGISTERS.
+//
+// What it computes is Algorithm 2 of the paper (Section 3): shells of bins of growing Chebyshev
+// radius around the query's bin, exact K-1 best others, stop once the k-th best is certified.
+// How it is laid out for CDNA4:
+//   * the shell walk is wave-uniform: all 64 lanes step through the same column offsets
+//     (offsets in the first DB-1 binning dimensions) of the same shell together.  Queries of a
+//     tile are consecutive in bin order, so the bins they need for one column offset form one
+//     contiguous range of sorted points; it is staged through LDS in chunks with coalesced
+//     structure-of-arrays loads, and each lane scans only its own sub-range of the chunk;
+//   * a candidate that beats the lane's current k-th best is appended to a small per-lane
+//     pending buffer in LDS (one write, no ordering work).  When any lane's buffer is full, and
+//     at the end of every shell, all lanes absorb their pending keys into the sorted register
+//     list with a fixed merging network (no data-dependent addressing, no LDS round trips);
+//   * keys are 64-bit (distance bits << 32 | original index); slots beyond K-1 are pinned with
+//     zero keys so that the last register is always the (K-1)-th best;
+//   * finished rows leave through LDS so that each output row is written as contiguous bytes;
+//   * lanes still uncertified when few are left are handed to the list kernel.
+#pragma once
+#include "fg_query.hpp"
+#include "fg_sortnet.hpp"
+
+namespace fg {
+
+constexpr int kPend = 16;   // pending keys per lane between two merges
+constexpr int kUnroll = 4;  // candidates per lane per pass of the scan loop (independent LDS reads in flight)
+
+// staged point = its D coordinates followed by its original index, padded to whole float4s
+template <int D> constexpr int stage_vecs() { return (D + 1 + 3) / 4; }
+
+template <int D, int DB, int KC, bool COUNT>
+__global__ void __launch_bounds__(kQueryBlock)
+k_query_tile_sorted(QueryArgs a)
+{
+    // LDS: [pending kPend x 64 keys][stage (D+1) x kStageChunk words]; re-used at the end as
+    //      [rows 64 words][sorted lists KC x 64 keys]
+    extern __shared__ uint64_t lds64[];
+    const int lane = threadIdx.x;
+    uint64_t* pend_lds = lds64 + lane;
+    constexpr int NV = stage_vecs<D>();
+    float4* stage = reinterpret_cast<float4*>(lds64 + kPend * kQueryBlock);   // [kStageChunk][NV]
+
+    const int32_t cap = a.k - 1;          // 0 <= cap <= KC
+    const int32_t p = blockIdx.x * kQueryBlock + lane;
+    const bool valid = p < a.n;
+    LaneGeom<D, DB> s;
+    s.init_geom(a, valid ? p : a.n - 1);  // dead lanes shadow the last point, never scan or write
+    bool active = valid && cap > 0;
+
+#ifdef FG_TILE_PROF
+    long long t_all = clock64(), t_setup = 0, t_stage = 0, t_scan = 0, t_absorb = 0, t_out = 0, tt;
+    int n_cols = 0, n_chunks = 0, n_iter = 0, n_absorb = 0, last_R = 0;
+#define PROF_T0 tt = clock64();
+#define PROF_ADD(x) x += clock64() - tt;
+#else
+#define PROF_T0
+#define PROF_ADD(x)
+#endif
+    uint64_t best[KC];
+#pragma unroll
+    for (int i = 0; i < KC; ++i) best[i] = (i < KC - cap) ? 0ull : ~0ull;
+    int32_t cnt = 0, cand = 0;
+
+    auto absorb = [&]() {
+        uint64_t pend[kPend];
+#pragma unroll
+        for (int i = 0; i < kPend; ++i) {
+            const uint64_t v = pend_lds[i * kQueryBlock];
+            pend[i] = i < cnt ? v : ~0ull;
+        }
+        net_sort<kPend>(pend);
+        net_absorb<KC, kPend>(best, pend);
+        cnt = 0;
+        s.tau = best[KC - 1];
+    };
+
+    for (int32_t R = 0;; ++R) {   // ends at the latest at R = n_bins - 1, when every lane's cube covers its grid
+        const int32_t side = 2 * R + 1;
+        int32_t ncols = 1;
+#pragma unroll
+        for (int c = 0; c < DB - 1; ++c) ncols *= side;
+        for (int32_t t = 0; t < ncols; ++t) {
+            PROF_T0
+#ifdef FG_TILE_PROF
+            ++n_cols; last_R = R;
+#endif
+            // column offsets, wave-uniform; digit v of t maps to 0, +1, -1, +2, -2, ... (centre first)
+            int32_t o[DB - 1];
+            bool surf = false;
+            {
+                int32_t rem = t;
+#pragma unroll
+                for (int c = DB - 2; c >= 0; --c) {
+                    const int32_t v = rem % side;
+                    rem /= side;
+                    o[c] = (v & 1) ? ((v + 1) >> 1) : -(v >> 1);
+                    surf = surf || o[c] == R || o[c] == -R;
+                }
+            }
+            bool ok = active;
+            float partial = 0.0f;
+            int32_t flat = 0;
+#pragma unroll
+            for (int c = 0; c < DB - 1; ++c) {
+                const int32_t j = s.cc[c] + o[c];
+                ok = ok && j >= 0 && j < s.neff[c];
+                const float g = s.gap(c, j, o[c]);
+                partial += g * g;
+                flat = flat * a.n_bins + j;
+            }
+            ok = ok && !s.cannot_improve(partial);
+            int32_t a1 = 0, b1 = 0, a2 = 0, b2 = 0;
+            if (ok) {
+                const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
+                const int32_t row = s.seg_cell0 + flat * a.n_bins;
+                if (surf) {
+                    const int32_t za = cz - R < 0 ? 0 : cz - R;
+                    const int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
+                    a1 = a.bounds[row + za];
+                    b1 = a.bounds[row + zb + 1];
+                } else {
+                    if (cz - R >= 0) {
+                        const float g = s.gap(DB - 1, cz - R, -R);
+                        if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[row + cz - R]; b1 = a.bounds[row + cz - R + 1]; }
+                    }
+                    if (cz + R <= nz - 1) {
+                        const float g = s.gap(DB - 1, cz + R, R);
+                        if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[row + cz + R]; b2 = a.bounds[row + cz + R + 1]; }
+                    }
+                }
+            }
+            int32_t lo = 0x7fffffff, hi = 0;
+            if (b1 > a1) { lo = a1; hi = b1; }
+            if (b2 > a2) { lo = a2 < lo ? a2 : lo; hi = b2 > hi ? b2 : hi; }
+            const int32_t PA = wave_min_i32(lo), PB = wave_max_i32(hi);
+            PROF_ADD(t_setup)
+            for (int32_t base = PA; base < PB; base += kStageChunk) {
+                const int32_t cnt_pts = PB - base < kStageChunk ? PB - base : kStageChunk;
+                PROF_T0
+#ifdef FG_TILE_PROF
+                ++n_chunks;
+#endif
+                __syncthreads();
+                for (int32_t i = lane; i < cnt_pts; i += kQueryBlock) {
+                    float w[NV * 4];
+#pragma unroll
+                    for (int c = 0; c < NV * 4; ++c) w[c] = 0.0f;
+#pragma unroll
+                    for (int c = 0; c < D; ++c) w[c] = a.soa[(int64_t)c * a.soa_stride + base + i];
+                    w[D] = __int_as_float(a.perm[base + i]);
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) stage[i * NV + v] = make_float4(w[4 * v], w[4 * v + 1], w[4 * v + 2], w[4 * v + 3]);
+                }
+                __syncthreads();
+                PROF_ADD(t_stage)
+                PROF_T0
+                // this lane's two sub-ranges clipped to the chunk, walked one after the other
+                const int32_t top = base + cnt_pts;
+                int32_t q = a1 > base ? a1 : base, e = b1 < top ? b1 : top;
+                int32_t q2 = a2 > base ? a2 : base, e2 = b2 < top ? b2 : top;
+                for (;;) {
+                    if (q >= e && q2 < e2) { q = q2; e = e2; q2 = e2; }
+                    const int32_t rem = e - q;
+                    if (!__any(rem > 0)) break;
+                    float w[kUnroll][NV * 4];
+#pragma unroll
+                    for (int u = 0; u < kUnroll; ++u) {
+                        int32_t i = q + u - base;                       // clamped: the read is always inside the chunk
+                        i = i < 0 ? 0 : (i > cnt_pts - 1 ? cnt_pts - 1 : i);
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) {
+                            const float4 f = stage[i * NV + v];
+                            w[u][4 * v] = f.x; w[u][4 * v + 1] = f.y; w[u][4 * v + 2] = f.z; w[u][4 * v + 3] = f.w;
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < kUnroll; ++u) {
+                        float diff = s.x[0] - w[u][0];
+                        float d2 = diff * diff;
+#pragma unroll
+                        for (int c = 1; c < D; ++c) {
+                            diff = s.x[c] - w[u][c];
+                            d2 = d2 + diff * diff;
+                        }
+                        const bool live = u < rem && q + u != p;
+                        if (COUNT) cand += live;
+                        const uint32_t bits = __float_as_uint(d2);
+                        const uint64_t key = ((uint64_t)bits << 32) | (uint32_t)__float_as_int(w[u][D]);
+                        if (live && key < s.tau) {
+                            pend_lds[cnt * kQueryBlock] = key;
+                            ++cnt;
+                        }
+                    }
+                    q += kUnroll;
+#ifdef FG_TILE_PROF
+                    ++n_iter;
+                    if (__any(cnt > kPend - kUnroll)) { long long t2 = clock64(); absorb(); t_absorb += clock64() - t2; ++n_absorb; }
+#else
+                    if (__any(cnt > kPend - kUnroll)) absorb();
+#endif
+                }
+                PROF_ADD(t_scan)
+            }
+        }
+        PROF_T0
+        if (__any(cnt > 0)) absorb();
+        PROF_ADD(t_absorb)
+        if (active && s.certified(R)) active = false;
+        const int32_t n_active = __popcll(__ballot(active));
+        if (n_active == 0) break;
+        if (R >= 1 && n_active <= kDeferLanes) break;
+    }
+
+    // unfinished lanes go to the work list (wave-aggregated append)
+    const uint64_t mask = __ballot(active);
+    if (mask) {
+        int32_t base = 0;
+        const int leader = __ffsll((unsigned long long)mask) - 1;
+        if (lane == leader) base = atomicAdd(a.work_count, __popcll(mask));
+        base = __shfl(base, leader, 64);
+        if (active) a.work_list[base + __popcll(mask & ((1ull << lane) - 1))] = p;
+    }
+
+    // finished rows: registers -> LDS -> contiguous row writes
+    PROF_T0
+    __syncthreads();
+    int32_t* rows_lds = reinterpret_cast<int32_t*>(lds64);
+    uint64_t* dump = lds64 + kQueryBlock / 2 + lane;     // after the 64 row words
+    const int32_t my_row = valid ? a.perm[p] : -1;
+    rows_lds[lane] = (valid && !active) ? my_row : -1;
+#pragma unroll
+    for (int i = 0; i < KC; ++i) dump[i * kQueryBlock] = best[i];
+#ifndef FG_TILE_PROF
+    if (COUNT && valid) a.out_cand[my_row] = cand;
+#endif
+    __syncthreads();
+    const int32_t k = a.k;
+    const int32_t per_iter = k >= kQueryBlock ? 1 : kQueryBlock / k;    // rows written per pass
+    const int32_t sub = lane / k;                                       // which of them this lane serves
+    const int32_t j0 = lane - sub * k;                                  // slot inside the row
+    for (int32_t r0 = 0; r0 < kQueryBlock; r0 += per_iter) {
+        const int32_t ql = r0 + sub;
+        if (sub >= per_iter || ql >= kQueryBlock) continue;
+        const int32_t row = rows_lds[ql];
+        if (row < 0) continue;
+        for (int32_t j = j0; j < k; j += kQueryBlock) {
+            int32_t oi = row;
+            float od = 0.0f;
+            if (j > 0) {
+                const uint64_t key = lds64[kQueryBlock / 2 + (KC - cap + j - 1) * kQueryBlock + ql];
+                const bool real = key != ~0ull;
+                oi = real ? (int32_t)(uint32_t)key : -1;
+                od = real ? __uint_as_float((uint32_t)(key >> 32)) : 0.0f;
+            }
+            a.out_idx[(int64_t)row * k + j] = oi;
+            a.out_d2[(int64_t)row * k + j] = od;
+        }
+    }
+#ifdef FG_TILE_PROF
+    PROF_ADD(t_out)
+    if (COUNT && lane == 0 && (blockIdx.x + 1) * 64 <= a.n) {
+        __syncthreads();
+        int32_t* pr = a.out_cand + blockIdx.x * 64;   // debug build only: the tile's 64 count slots carry the profile
+        pr[0] = (int32_t)((clock64() - t_all) >> 4); pr[1] = (int32_t)(t_setup >> 4); pr[2] = (int32_t)(t_stage >> 4);
+        pr[3] = (int32_t)(t_scan >> 4); pr[4] = (int32_t)(t_absorb >> 4); pr[5] = last_R; pr[6] = n_cols;
+        pr[7] = n_chunks; pr[8] = n_iter; pr[9] = n_absorb; pr[10] = (int32_t)(t_out >> 4);
+        pr[11] = __popcll(mask);
+    }
+#endif
+}
+
+template <int KC, int D>
+constexpr size_t tile_sorted_lds_bytes()
+{
+    const size_t scan = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * kStageChunk;
+    const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kQueryBlock * 8;
+    return scan > out ? scan : out;
+}
+
+}  // namespace fg

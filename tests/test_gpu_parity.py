@@ -152,6 +152,32 @@ def test_deterministic_across_runs():
     assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
 
 
+def test_tile_and_list_kernels_both_run_and_agree_with_the_plain_walk():
+    """Default path = tile kernel + list kernel for the queries it defers; query_algo = 1 sends
+    every query through the one-lane-per-query walk.  Isolated points far from a dense core need
+    many shells, so some queries must reach the list kernel."""
+    rng = np.random.Generator(np.random.PCG64(29))
+    core = rng.standard_normal((6000, 3)) * 0.05
+    far = rng.random((600, 3)) * 20.0 - 10.0
+    x = np.ascontiguousarray(np.concatenate([core, far]).astype(np.float32))
+    rng.shuffle(x, axis=0)
+    rs = np.array([0, 4000, x.shape[0]], dtype=np.int32)
+    k = 12
+    oi, od = oracle.knn(x, rs, k)
+    xt, rt = torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV)
+    for nb in (0, 40):
+        bn = B.fg_bin_points(xt, rt, k, nb, 3 if nb else 0)
+        gi, gd = B.fg_query_binned(bn, rt, k)
+        torch.cuda.synchronize()
+        deferred = int(bn.work_count.item())
+        assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "tile+list nb=%d" % nb)
+        assert 0 < deferred < x.shape[0]
+        bn.raw.query_algo = 1
+        gi, gd = B.fg_query_binned(bn, rt, k)
+        torch.cuda.synchronize()
+        assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "plain walk nb=%d" % nb)
+
+
 def test_candidate_counts():
     """n_bins = 1: every query scans its whole row split minus itself (brute force through the
     same kernel); finer grids scan fewer candidates, never fewer than k-1."""
