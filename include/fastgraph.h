@@ -137,14 +137,18 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
 /* Backward of the squared distances (Section 3, last paragraph):
  *   grad_coords[v][c]  = sum_j grad_d2[v][j] * 2 * (x[v][c] - x[idx[v][j]][c])
  *                      - sum_{(w,j): idx[w][j] = v} grad_d2[w][j] * 2 * (x[w][c] - x[v][c])
- * over entries with idx >= 0.
+ * over entries with 0 <= idx < n (negative = padding; out-of-range entries are ignored).
  *   grad_d2 [n][k] float32, idx [n][k] int32 (as returned by the forward), coords [n][d]
  *   grad_coords [n][d] float32, overwritten (zero-filled by the call, then accumulated with
  *   float32 atomics: the summation order, hence the last bits, may differ between runs).
- * workspace may be NULL (none is needed). */
+ *   row_splits [n_segments+1], workspace: optional.  With both given (workspace as for
+ *   fg_binned_select_knn with this k and automatic bins) the rows are processed in bin order and
+ *   contributions to the same destination are combined in LDS before they reach memory, which
+ *   is several times faster; with row_splits == NULL or workspace == NULL every contribution is
+ *   one global atomic.  A workspace that is given but too small is FG_ERR_WORKSPACE. */
 fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float* coords,
-                          int64_t n, int32_t d, int32_t k, float* grad_coords,
-                          void* workspace, size_t workspace_bytes, void* stream);
+                          const int32_t* row_splits, int64_t n, int32_t d, int32_t n_segments, int32_t k,
+                          float* grad_coords, void* workspace, size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -71,7 +71,7 @@ def lib() -> ctypes.CDLL:
         L.fg_query_binned.restype = ctypes.c_int
         L.fg_query_binned.argtypes = [ctypes.POINTER(_Binning), vp, i64, i32, i32, i32, vp, vp, vp, vp]
         L.fg_knn_backward.restype = ctypes.c_int
-        L.fg_knn_backward.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp, sz, vp]
+        L.fg_knn_backward.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -239,7 +239,10 @@ def fg_binned_select_knn_counted(coords: torch.Tensor, row_splits: torch.Tensor,
 
 
 def fg_knn_backward(grad_d2: torch.Tensor, idx: torch.Tensor, coords: torch.Tensor,
-                    grad_coords: torch.Tensor | None = None) -> torch.Tensor:
+                    row_splits: torch.Tensor | None = None, grad_coords: torch.Tensor | None = None,
+                    workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """With row_splits the bin-ordered LDS-combining kernel runs (a workspace is allocated if none
+    is passed); without, the plain atomic scatter."""
     grad_d2 = _dev(grad_d2, torch.float32, "grad_d2")
     idx = _dev(idx, torch.int32, "idx")
     coords = _dev(coords, torch.float32, "coords")
@@ -249,6 +252,15 @@ def fg_knn_backward(grad_d2: torch.Tensor, idx: torch.Tensor, coords: torch.Tens
         raise ValueError("grad_d2 and idx must be [n, k]")
     if grad_coords is None:
         grad_coords = torch.empty((n, d), dtype=torch.float32, device=coords.device)
-    _check(lib().fg_knn_backward(_ptr(grad_d2), _ptr(idx), _ptr(coords), n, d, k, _ptr(grad_coords),
-                                 None, 0, _stream()), "fg_knn_backward")
+    s = 0
+    if row_splits is not None:
+        row_splits = _dev(row_splits, torch.int32, "row_splits")
+        s = row_splits.numel() - 1
+        if workspace is None:
+            workspace = alloc_workspace(n, d, s, k, 0, 0, coords.device)
+    else:
+        workspace = None
+    _check(lib().fg_knn_backward(_ptr(grad_d2), _ptr(idx), _ptr(coords), _ptr(row_splits), n, d, s, k,
+                                 _ptr(grad_coords), _ptr(workspace),
+                                 0 if workspace is None else workspace.numel(), _stream()), "fg_knn_backward")
     return grad_coords

@@ -264,15 +264,23 @@ fg_status fg_binned_select_knn_counted(const float* coords, const int32_t* row_s
 }
 
 fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float* coords,
-                          int64_t n, int32_t d, int32_t k, float* grad_coords,
-                          void* workspace, size_t workspace_bytes, void* stream)
+                          const int32_t* row_splits, int64_t n, int32_t d, int32_t n_segments, int32_t k,
+                          float* grad_coords, void* workspace, size_t workspace_bytes, void* stream)
 {
-    (void)workspace; (void)workspace_bytes;
-    fg_status st = check_problem(n, d, 1, k);
+    fg_status st = check_problem(n, d, n_segments < 1 ? 1 : n_segments, k);
     if (st != FG_OK) return st;
     if (n == 0) return FG_OK;
     if (!grad_d2 || !idx || !coords || !grad_coords) return FG_ERR_NULL;
-    hipError_t e = launch_backward(grad_d2, idx, coords, (int32_t)n, d, k, grad_coords, (hipStream_t)stream);
+    const int32_t* perm = nullptr;
+    if (row_splits && workspace && n_segments >= 1) {
+        // bin the points once more to get a spatially coherent row order (the forward's workspace
+        // is scratch by contract, so nothing of it is assumed to survive)
+        fg_binning view;
+        st = fg_bin_points(coords, row_splits, n, d, n_segments, k, 0, 0, workspace, workspace_bytes, &view, stream);
+        if (st != FG_OK) return st;
+        perm = view.perm;
+    }
+    hipError_t e = launch_backward(grad_d2, idx, coords, perm, (int32_t)n, d, k, grad_coords, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }
 

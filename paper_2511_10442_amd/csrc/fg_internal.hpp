@@ -39,8 +39,9 @@ hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_
 // d = 2..10, d_bin = 2..min(d,5)
 hipError_t launch_query(const QueryArgs& a, int32_t d, int32_t d_bin, hipStream_t stream);
 
-hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, int32_t n,
-                           int32_t d, int32_t k, float* grad_coords, hipStream_t stream);
+// perm != nullptr: rows are taken in bin order and combined in LDS; nullptr: plain atomic scatter
+hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, const int32_t* perm,
+                           int32_t n, int32_t d, int32_t k, float* grad_coords, hipStream_t stream);
 
 // Segment of a (sorted or original) position: largest s with row_splits[s] <= p, skipping empty
 // segments by construction (row_splits[s+1] > p).

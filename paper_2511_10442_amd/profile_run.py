@@ -47,7 +47,8 @@ def main() -> int:
     x = torch.from_numpy(w.coords).to(dev)
     rs = torch.from_numpy(w.row_splits).to(dev)
     n, d, k, s = w.n, w.d, w.k, w.n_segments
-    ws = B.alloc_workspace(n, d, s, k, args.n_bins, args.d_bin, dev)
+    ws_bytes = max(B.fg_workspace_size(n, d, s, k, args.n_bins, args.d_bin), B.fg_workspace_size(n, d, s, k))
+    ws = torch.empty(max(ws_bytes, 256), dtype=torch.uint8, device=dev)
     out_idx = torch.empty((n, k), dtype=torch.int32, device=dev)
     out_d2 = torch.empty((n, k), dtype=torch.float32, device=dev)
     g = torch.from_numpy(w.grad_d2).to(dev) if w.grad_d2 is not None else torch.ones((n, k), device=dev)
@@ -62,11 +63,11 @@ def main() -> int:
     elif args.stage == "backward":
         B.fg_binned_select_knn(x, rs, k, args.n_bins, args.d_bin, ws, out_idx, out_d2)
         for _ in range(args.reps):
-            B.fg_knn_backward(g, out_idx, x, grad)
+            B.fg_knn_backward(g, out_idx, x, rs, grad, ws)
     else:
         for _ in range(args.reps):
             B.fg_binned_select_knn(x, rs, k, args.n_bins, args.d_bin, ws, out_idx, out_d2)
-            B.fg_knn_backward(g, out_idx, x, grad)
+            B.fg_knn_backward(g, out_idx, x, rs, grad, ws)
     torch.cuda.synchronize()
     print("profile_run done: config %d stage %s reps %d" % (args.config, args.stage, args.reps))
     return 0

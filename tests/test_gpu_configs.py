@@ -103,9 +103,9 @@ def grad_close(g_gpu, g_ref, abs_sum, rtol=1e-5):
     assert err.max() <= rtol * max(np.abs(g_ref).max(), 1e-30)
 
 
-def backward_gpu(g, idx, x):
+def backward_gpu(g, idx, x, rs):
     out = B.fg_knn_backward(torch.from_numpy(g).to(DEV), torch.from_numpy(np.ascontiguousarray(idx)).to(DEV),
-                            torch.from_numpy(x).to(DEV))
+                            torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV))
     torch.cuda.synchronize()
     return out.cpu().numpy()
 
@@ -148,7 +148,7 @@ def test_config2_full_forward_and_backward():
     assert np.array_equal(gi, oi) and np.array_equal(gd.view(np.uint32), od.view(np.uint32))
     check_properties(w, gi, gd)
     ref, asum = oracle.knn_backward(w.grad_d2, oi, w.coords)
-    grad_close(backward_gpu(w.grad_d2, oi, w.coords), ref, asum)
+    grad_close(backward_gpu(w.grad_d2, oi, w.coords, w.row_splits), ref, asum)
     nb, db = B.fg_auto_n_bins(w.n, w.n_segments, w.k, w.d, mode=0)   # paper: 14 bins over 4 dims
     gi2, gd2 = forward(w, nb, db)
     assert np.array_equal(gi2, oi) and np.array_equal(gd2.view(np.uint32), od.view(np.uint32))
@@ -171,10 +171,10 @@ def test_config3_backward():
     rows = sample_rows(w.n, 20000, seed=313)
     idx, _, _ = sampled_graph(w, rows)
     ref, asum = oracle.knn_backward(w.grad_d2, idx, w.coords)
-    grad_close(backward_gpu(w.grad_d2, idx, w.coords), ref, asum)
+    grad_close(backward_gpu(w.grad_d2, idx, w.coords, w.row_splits), ref, asum)
     idx = random_in_segment_graph(w, seed=323)
     ref, asum = oracle.knn_backward(w.grad_d2, idx, w.coords)
-    grad_close(backward_gpu(w.grad_d2, idx, w.coords), ref, asum)
+    grad_close(backward_gpu(w.grad_d2, idx, w.coords, w.row_splits), ref, asum)
 
 
 def test_config4_forward():
@@ -217,8 +217,8 @@ def test_config5_backward():
     rows = sample_rows(w.n, 8000, seed=515)
     idx, _, _ = sampled_graph(w, rows)
     ref, asum = oracle.knn_backward(w.grad_d2, idx, w.coords)
-    grad_close(backward_gpu(w.grad_d2, idx, w.coords), ref, asum)
+    grad_close(backward_gpu(w.grad_d2, idx, w.coords, w.row_splits), ref, asum)
     idx = random_in_segment_graph(w, seed=525)
     ref, asum = oracle.knn_backward(w.grad_d2, idx, w.coords)
-    grad_close(backward_gpu(w.grad_d2, idx, w.coords), ref, asum)
+    grad_close(backward_gpu(w.grad_d2, idx, w.coords, w.row_splits), ref, asum)
     _cache.clear()

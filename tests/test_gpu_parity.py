@@ -236,9 +236,11 @@ def test_binning_invariants(d, nb, db):
 # --------------------------------------------------------------------------- #
 # backward
 # --------------------------------------------------------------------------- #
-def gpu_backward(g, idx, x):
+def gpu_backward(g, idx, x, rs=None):
+    """rs given: bin-ordered kernel that combines contributions in LDS; None: plain atomic scatter."""
     out = B.fg_knn_backward(torch.from_numpy(g).to(DEV), torch.from_numpy(idx).to(DEV),
-                            torch.from_numpy(x).to(DEV))
+                            torch.from_numpy(x).to(DEV),
+                            None if rs is None else torch.from_numpy(rs).to(DEV))
     torch.cuda.synchronize()
     return out.cpu().numpy()
 
@@ -252,6 +254,22 @@ def test_backward_small(d, k):
     g = W.upstream_grad(n, k, seed=43)
     ref, asum = oracle.knn_backward(g, idx, x)
     grad_close(gpu_backward(g, idx, x), ref, asum)
+    grad_close(gpu_backward(g, idx, x, rs), ref, asum)
+
+
+def test_backward_hash_table_overflow_and_hot_destination():
+    """More distinct destinations per block than the LDS table holds (random far neighbours), and one
+    destination shared by every row: both must still add up."""
+    n, k, d = 6000, 64, 3
+    x, rs = W.uniform(n, d, seed=61)
+    rng = np.random.Generator(np.random.PCG64(62))
+    idx = rng.integers(0, n, size=(n, k)).astype(np.int32)
+    idx[:, 5] = 17
+    idx[rng.random((n, k)) < 0.05] = -1
+    g = W.upstream_grad(n, k, seed=63)
+    ref, asum = oracle.knn_backward(g, idx, x)
+    grad_close(gpu_backward(g, idx, x, rs), ref, asum)
+    grad_close(gpu_backward(g, idx, x), ref, asum)
 
 
 def test_backward_overwrites_and_ignores_padding():
@@ -259,7 +277,12 @@ def test_backward_overwrites_and_ignores_padding():
     idx = np.full((100, 4), -1, dtype=np.int32)
     g = W.upstream_grad(100, 4, seed=52)
     out = B.fg_knn_backward(torch.from_numpy(g).to(DEV), torch.from_numpy(idx).to(DEV),
-                            torch.from_numpy(x).to(DEV),
+                            torch.from_numpy(x).to(DEV), None,
+                            torch.full((100, 3), 7.0, dtype=torch.float32, device=DEV))
+    torch.cuda.synchronize()
+    assert np.all(out.cpu().numpy() == 0.0)
+    out = B.fg_knn_backward(torch.from_numpy(g).to(DEV), torch.from_numpy(idx).to(DEV),
+                            torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV),
                             torch.full((100, 3), 7.0, dtype=torch.float32, device=DEV))
     torch.cuda.synchronize()
     assert np.all(out.cpu().numpy() == 0.0)

@@ -90,9 +90,10 @@ def test_argument_validation_without_gpu():
     assert L.fg_binned_select_knn(8, 8, 10, 3, 1, 4, 0, 0, None, 8, 256, 1 << 30, None) == B.FG_ERR_NULL
     assert L.fg_binned_select_knn(8, 8, 10, 12, 1, 4, 0, 0, 8, 8, 256, 1 << 30, None) == B.FG_ERR_UNSUPPORTED
     assert L.fg_binned_select_knn(None, None, 0, 3, 1, 4, 0, 0, None, None, None, 0, None) == B.FG_OK  # n == 0
-    assert L.fg_knn_backward(None, 8, 8, 10, 3, 4, 8, None, 0, None) == B.FG_ERR_NULL
-    assert L.fg_knn_backward(8, 8, 8, 10, 3, 200, 8, None, 0, None) == B.FG_ERR_UNSUPPORTED
-    assert L.fg_knn_backward(None, None, None, 0, 3, 4, None, None, 0, None) == B.FG_OK
+    assert L.fg_knn_backward(None, 8, 8, None, 10, 3, 1, 4, 8, None, 0, None) == B.FG_ERR_NULL
+    assert L.fg_knn_backward(8, 8, 8, None, 10, 3, 1, 200, 8, None, 0, None) == B.FG_ERR_UNSUPPORTED
+    assert L.fg_knn_backward(8, 8, 8, 8, 10, 3, 1, 4, 8, 256, 16, None) == B.FG_ERR_WORKSPACE
+    assert L.fg_knn_backward(None, None, None, None, 0, 3, 1, 4, None, None, 0, None) == B.FG_OK
     assert L.fg_query_binned(None, 8, 10, 3, 1, 4, 8, 8, None, None) == B.FG_ERR_NULL
 
 
