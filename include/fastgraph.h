@@ -87,6 +87,9 @@ typedef struct {
     int32_t* work_count;       /* [1]  scratch of the query stage */
     int32_t query_algo;        /* 0 (set by fg_bin_points): tile kernel + list kernel; 1: the one-lane-per-query
                                   shell walk for every query (slower; same result; kept for cross-checking) */
+    int32_t defer_lanes;       /* tuning knob of the tile kernel, 0..64 (set by fg_bin_points): after shell 1 a
+                                  wavefront goes on to the next shell only while more than this many of its 64
+                                  queries are unfinished; the rest go to the list kernel.  Result-neutral. */
 } fg_binning;
 
 /* Spatial partition + counting sort (Section 3: "points are sorted by bin assignments and

@@ -39,7 +39,8 @@ class _Binning(ctypes.Structure):
                 ("seg_geom", ctypes.c_void_p), ("soa_stride", ctypes.c_int64),
                 ("cells_per_segment", ctypes.c_int64), ("n_bins", ctypes.c_int32),
                 ("d_bin", ctypes.c_int32), ("work_list", ctypes.c_void_p),
-                ("work_count", ctypes.c_void_p), ("query_algo", ctypes.c_int32)]
+                ("work_count", ctypes.c_void_p), ("query_algo", ctypes.c_int32),
+                ("defer_lanes", ctypes.c_int32)]
 
 
 _lib = None

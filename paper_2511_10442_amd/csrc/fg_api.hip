@@ -39,6 +39,7 @@ constexpr size_t kAlign = 256;
 constexpr double kTunedCellsPerK = 8.0;
 constexpr int32_t kTunedMaxDBin = 3;
 constexpr int32_t kTunedMaxBins = 256;
+constexpr int32_t kDefaultDeferLanes = 63;
 constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -194,6 +195,7 @@ fg_status fg_bin_points(const float* coords, const int32_t* row_splits, int64_t 
     view->work_list = (int32_t*)(ws + L.work_list);
     view->work_count = (int32_t*)(ws + L.work_count);
     view->query_algo = 0;
+    view->defer_lanes = kDefaultDeferLanes;
     if (n == 0) return FG_OK;
     hipError_t e = launch_binning(coords, row_splits, (int32_t)n, d, n_segments, n_bins, d_bin, L.total_bins,
                                   (uint32_t*)(ws + L.keys), (float*)(ws + L.geom), (int32_t*)(ws + L.bin_idx),
@@ -224,6 +226,7 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
     a.soa_stride = view->soa_stride; a.n = (int32_t)n; a.n_segments = n_segments; a.k = k;
     a.n_bins = view->n_bins; a.cells_per_segment = (int32_t)view->cells_per_segment;
     a.work_list = view->work_list; a.work_count = view->work_count; a.algo = view->query_algo == 1 ? 1 : 0;
+    a.defer_lanes = view->defer_lanes < 0 ? 0 : (view->defer_lanes > 64 ? 64 : view->defer_lanes);
     hipError_t e = launch_query(a, d, view->d_bin, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }

@@ -27,6 +27,7 @@ struct QueryArgs {
     int32_t n_bins;
     int32_t cells_per_segment;
     int32_t algo;              // 0: tile kernel + list kernel, 1: one lane per query for everything
+    int32_t defer_lanes;       // tile kernel: go on past shell 1 only while more lanes than this are unfinished
 };
 
 // Host-side launchers, one per translation unit.  Each returns hipGetLastError() of its launches.

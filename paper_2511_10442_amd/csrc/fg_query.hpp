@@ -299,17 +299,30 @@ __device__ __forceinline__ void write_row(ShellSearch<D, DB, COUNT>& s, const Qu
 // hands them to the list kernel below, so that a handful of far-searching queries (isolated
 // points) does not keep 64 lanes busy.
 
-constexpr int kDeferLanes = 48;    // after shell 1, go on to the next shell only while more lanes than this are unfinished
 
+// Wave-wide min / max of one int per lane with DPP row shifts and row broadcasts (6 VALU
+// operations and one readlane each); the result is uniform.
 __device__ __forceinline__ int32_t wave_min_i32(int32_t v)
 {
-    for (int o = 32; o > 0; o >>= 1) { int32_t t = __shfl_xor(v, o, 64); v = t < v ? t : v; }
-    return v;
+    const int32_t id = 0x7fffffff;
+    v = min(v, __builtin_amdgcn_update_dpp(id, v, 0x111, 0xf, 0xf, false));   // row_shr:1
+    v = min(v, __builtin_amdgcn_update_dpp(id, v, 0x112, 0xf, 0xf, false));   // row_shr:2
+    v = min(v, __builtin_amdgcn_update_dpp(id, v, 0x114, 0xf, 0xf, false));   // row_shr:4
+    v = min(v, __builtin_amdgcn_update_dpp(id, v, 0x118, 0xf, 0xf, false));   // row_shr:8
+    v = min(v, __builtin_amdgcn_update_dpp(id, v, 0x142, 0xa, 0xf, false));   // row_bcast:15 into rows 1 and 3
+    v = min(v, __builtin_amdgcn_update_dpp(id, v, 0x143, 0xc, 0xf, false));   // row_bcast:31 into rows 2 and 3
+    return __builtin_amdgcn_readlane(v, 63);
 }
 __device__ __forceinline__ int32_t wave_max_i32(int32_t v)
 {
-    for (int o = 32; o > 0; o >>= 1) { int32_t t = __shfl_xor(v, o, 64); v = t > v ? t : v; }
-    return v;
+    const int32_t id = (int32_t)0x80000000;
+    v = max(v, __builtin_amdgcn_update_dpp(id, v, 0x111, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(id, v, 0x112, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(id, v, 0x114, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(id, v, 0x118, 0xf, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(id, v, 0x142, 0xa, 0xf, false));
+    v = max(v, __builtin_amdgcn_update_dpp(id, v, 0x143, 0xc, 0xf, false));
+    return __builtin_amdgcn_readlane(v, 63);
 }
 
 template <int D, int DB, bool COUNT>
@@ -400,7 +413,7 @@ k_query_tile(QueryArgs a)
         if (active && s.certified(R)) active = false;
         const int32_t n_active = __popcll(__ballot(active));
         if (n_active == 0) break;
-        if (R >= 1 && n_active <= kDeferLanes) break;
+        if (R >= 1 && n_active <= a.defer_lanes) break;
     }
 
     // unfinished lanes go to the work list (wave-aggregated append); the rest write their rows

@@ -129,8 +129,18 @@ k_query_list_wave(QueryArgs a)
                     const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
                     const int32_t row = s.seg_cell0 + flat * a.n_bins;
                     if (surf) {
-                        const int32_t za = cz - R < 0 ? 0 : cz - R;
-                        const int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
+                        int32_t za = cz - R < 0 ? 0 : cz - R;
+                        int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
+                        while (za < cz) {      // drop end bins of the run whose box is already too far
+                            const float g = s.gap(DB - 1, za, za - cz);
+                            if (!s.cannot_improve(partial + g * g)) break;
+                            ++za;
+                        }
+                        while (zb > cz) {
+                            const float g = s.gap(DB - 1, zb, zb - cz);
+                            if (!s.cannot_improve(partial + g * g)) break;
+                            --zb;
+                        }
                         a1 = a.bounds[row + za];
                         b1 = a.bounds[row + zb + 1];
                     } else {

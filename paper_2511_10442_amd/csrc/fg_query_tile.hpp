@@ -24,6 +24,8 @@
 namespace fg {
 
 constexpr int kPend = 16;   // pending keys per lane between two merges
+struct Ranges { int32_t a1, b1, a2, b2; };
+
 constexpr int kUnroll = 4;  // candidates per lane per pass of the scan loop (independent LDS reads in flight)
 
 // staged point = its D coordinates followed by its original index, padded to whole float4s
@@ -34,7 +36,7 @@ __global__ void __launch_bounds__(kQueryBlock)
 k_query_tile_sorted(QueryArgs a)
 {
     // LDS: [pending kPend x 64 keys][stage (D+1) x kStageChunk words]; re-used at the end as
-    //      [rows 64 words][sorted lists KC x 64 keys]
+    //      [rows 64 words][KC x 64 words of the sorted lists, indices first, distances second]
     extern __shared__ uint64_t lds64[];
     const int lane = threadIdx.x;
     uint64_t* pend_lds = lds64 + lane;
@@ -80,11 +82,8 @@ k_query_tile_sorted(QueryArgs a)
         int32_t ncols = 1;
 #pragma unroll
         for (int c = 0; c < DB - 1; ++c) ncols *= side;
-        for (int32_t t = 0; t < ncols; ++t) {
-            PROF_T0
-#ifdef FG_TILE_PROF
-            ++n_cols; last_R = R;
-#endif
+        // this lane's candidate ranges for column t of shell R: up to two runs of sorted positions
+        auto prepare = [&](int32_t t) -> Ranges {
             // column offsets, wave-uniform; digit v of t maps to 0, +1, -1, +2, -2, ... (centre first)
             int32_t o[DB - 1];
             bool surf = false;
@@ -115,8 +114,19 @@ k_query_tile_sorted(QueryArgs a)
                 const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
                 const int32_t row = s.seg_cell0 + flat * a.n_bins;
                 if (surf) {
-                    const int32_t za = cz - R < 0 ? 0 : cz - R;
-                    const int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
+                    int32_t za = cz - R < 0 ? 0 : cz - R;
+                    int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
+                    // drop end bins of the run whose box is already too far
+                    while (za < cz) {
+                        const float g = s.gap(DB - 1, za, za - cz);
+                        if (!s.cannot_improve(partial + g * g)) break;
+                        ++za;
+                    }
+                    while (zb > cz) {
+                        const float g = s.gap(DB - 1, zb, zb - cz);
+                        if (!s.cannot_improve(partial + g * g)) break;
+                        --zb;
+                    }
                     a1 = a.bounds[row + za];
                     b1 = a.bounds[row + zb + 1];
                 } else {
@@ -130,6 +140,20 @@ k_query_tile_sorted(QueryArgs a)
                     }
                 }
             }
+            return Ranges{a1, b1, a2, b2};
+        };
+        Ranges cur = prepare(0);
+        for (int32_t t = 0; t < ncols; ++t) {
+            PROF_T0
+#ifdef FG_TILE_PROF
+            ++n_cols; last_R = R;
+#endif
+            // the next column's bin boundaries are requested before this column is scanned, so
+            // their latency hides behind the scan (its pruning sees a k-th best one column old)
+            Ranges nxt = Ranges{0, 0, 0, 0};
+            if (t + 1 < ncols) nxt = prepare(t + 1);
+            const int32_t a1 = cur.a1, b1 = cur.b1, a2 = cur.a2, b2 = cur.b2;
+            cur = nxt;
             int32_t lo = 0x7fffffff, hi = 0;
             if (b1 > a1) { lo = a1; hi = b1; }
             if (b2 > a2) { lo = a2 < lo ? a2 : lo; hi = b2 > hi ? b2 : hi; }
@@ -164,13 +188,12 @@ k_query_tile_sorted(QueryArgs a)
                     const int32_t rem = e - q;
                     if (!__any(rem > 0)) break;
                     float w[kUnroll][NV * 4];
+                    const int32_t i0 = rem > 0 ? q - base : 0;       // reads past the lane's range stay inside the padded chunk
 #pragma unroll
                     for (int u = 0; u < kUnroll; ++u) {
-                        int32_t i = q + u - base;                       // clamped: the read is always inside the chunk
-                        i = i < 0 ? 0 : (i > cnt_pts - 1 ? cnt_pts - 1 : i);
 #pragma unroll
                         for (int v = 0; v < NV; ++v) {
-                            const float4 f = stage[i * NV + v];
+                            const float4 f = stage[(i0 + u) * NV + v];
                             w[u][4 * v] = f.x; w[u][4 * v + 1] = f.y; w[u][4 * v + 2] = f.z; w[u][4 * v + 3] = f.w;
                         }
                     }
@@ -209,7 +232,7 @@ k_query_tile_sorted(QueryArgs a)
         if (active && s.certified(R)) active = false;
         const int32_t n_active = __popcll(__ballot(active));
         if (n_active == 0) break;
-        if (R >= 1 && n_active <= kDeferLanes) break;
+        if (R >= 1 && n_active <= a.defer_lanes) break;
     }
 
     // unfinished lanes go to the work list (wave-aggregated append)
@@ -225,36 +248,40 @@ k_query_tile_sorted(QueryArgs a)
     // finished rows: registers -> LDS -> contiguous row writes
     PROF_T0
     __syncthreads();
+    // two passes (indices, then distances) so the transposition needs KC x 64 words, not keys
     int32_t* rows_lds = reinterpret_cast<int32_t*>(lds64);
-    uint64_t* dump = lds64 + kQueryBlock / 2 + lane;     // after the 64 row words
+    uint32_t* dump = reinterpret_cast<uint32_t*>(lds64) + kQueryBlock;     // [KC][64] after the 64 row words
     const int32_t my_row = valid ? a.perm[p] : -1;
     rows_lds[lane] = (valid && !active) ? my_row : -1;
-#pragma unroll
-    for (int i = 0; i < KC; ++i) dump[i * kQueryBlock] = best[i];
 #ifndef FG_TILE_PROF
     if (COUNT && valid) a.out_cand[my_row] = cand;
 #endif
-    __syncthreads();
     const int32_t k = a.k;
     const int32_t per_iter = k >= kQueryBlock ? 1 : kQueryBlock / k;    // rows written per pass
     const int32_t sub = lane / k;                                       // which of them this lane serves
     const int32_t j0 = lane - sub * k;                                  // slot inside the row
-    for (int32_t r0 = 0; r0 < kQueryBlock; r0 += per_iter) {
-        const int32_t ql = r0 + sub;
-        if (sub >= per_iter || ql >= kQueryBlock) continue;
-        const int32_t row = rows_lds[ql];
-        if (row < 0) continue;
-        for (int32_t j = j0; j < k; j += kQueryBlock) {
-            int32_t oi = row;
-            float od = 0.0f;
-            if (j > 0) {
-                const uint64_t key = lds64[kQueryBlock / 2 + (KC - cap + j - 1) * kQueryBlock + ql];
-                const bool real = key != ~0ull;
-                oi = real ? (int32_t)(uint32_t)key : -1;
-                od = real ? __uint_as_float((uint32_t)(key >> 32)) : 0.0f;
+#pragma unroll
+    for (int pass = 0; pass < 2; ++pass) {
+        if (pass) __syncthreads();
+#pragma unroll
+        for (int i = 0; i < KC; ++i) {
+            const bool real = best[i] != ~0ull;
+            const uint32_t word = pass == 0 ? (real ? (uint32_t)best[i] : 0xffffffffu)      // index or -1
+                                            : (real ? (uint32_t)(best[i] >> 32) : 0u);       // distance bits or 0.0f
+            dump[i * kQueryBlock + lane] = word;
+        }
+        __syncthreads();
+        for (int32_t r0 = 0; r0 < kQueryBlock; r0 += per_iter) {
+            const int32_t ql = r0 + sub;
+            if (sub >= per_iter || ql >= kQueryBlock) continue;
+            const int32_t row = rows_lds[ql];
+            if (row < 0) continue;
+            for (int32_t j = j0; j < k; j += kQueryBlock) {
+                uint32_t word = pass == 0 ? (uint32_t)row : 0u;             // slot 0: the row itself at distance 0
+                if (j > 0) word = dump[(KC - cap + j - 1) * kQueryBlock + ql];
+                if (pass == 0) a.out_idx[(int64_t)row * k + j] = (int32_t)word;
+                else a.out_d2[(int64_t)row * k + j] = __uint_as_float(word);
             }
-            a.out_idx[(int64_t)row * k + j] = oi;
-            a.out_d2[(int64_t)row * k + j] = od;
         }
     }
 #ifdef FG_TILE_PROF
@@ -273,8 +300,8 @@ k_query_tile_sorted(QueryArgs a)
 template <int KC, int D>
 constexpr size_t tile_sorted_lds_bytes()
 {
-    const size_t scan = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * kStageChunk;
-    const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kQueryBlock * 8;
+    const size_t scan = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (kStageChunk + kUnroll);
+    const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kQueryBlock * 4;
     return scan > out ? scan : out;
 }
 
