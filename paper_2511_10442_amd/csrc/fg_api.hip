@@ -34,11 +34,19 @@ namespace {
 
 constexpr size_t kAlign = 256;
 
-// fg_auto_n_bins mode 1: cells per row split = kTunedCellsPerK * n_elems / K, i.e. about
-// K / kTunedCellsPerK points per bin, over the first min(d, kTunedMaxDBin) dimensions.
-constexpr double kTunedCellsPerK = 8.0;
-constexpr int32_t kTunedMaxDBin = 3;
-constexpr int32_t kTunedMaxBins = 256;
+// fg_auto_n_bins mode 1.  The tile kernel is at its best when one shell around the query's bin
+// (3 bins per dimension) is enough for most queries, i.e. when the bin width is about the
+// radius r_K of the ball that holds K points at the mean density of a row split:
+//   r_K = extent * (K / (n_elems * V_d))^(1/d),  V_d = volume of the unit ball in d dimensions,
+// so bins per dimension = kTunedMargin * (n_elems * V_d / K)^(1/d).  Same functional form as
+// the paper's heuristic (a power 1/d of n_elems / K), with the constant 32 replaced by V_d and
+// the exponent taken over all d coordinates because the distance is.  Binning dimensions: all of
+// them up to 3; the first 3 for d = 4; the first 5 from d = 5 on (measured on uniform data).
+// From d = 6 on a cube of 3 bins per side wastes most of its volume outside the ball, and bins
+// of about 0.6 r_K searched two shells deep (with box pruning) measured faster.
+constexpr double kTunedMargin = 0.9;
+constexpr double kTunedMarginHighD = 1.6;
+constexpr int32_t kTunedMaxBins = 1024;
 constexpr int32_t kDefaultDeferLanes = 63;
 constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
 
@@ -145,11 +153,12 @@ fg_status fg_auto_n_bins(int64_t n, int32_t n_segments, int32_t k, int32_t d, in
         *d_bin = db;
         return FG_OK;
     }
-    // mode 1: same functional form, this build's constants (kTunedCellsPerK, kTunedMaxDBin, kTunedMaxBins)
-    const int32_t db = d < kTunedMaxDBin ? d : kTunedMaxDBin;
-    double cells = n_elems > 0 ? kTunedCellsPerK * n_elems / (double)k : 1.0;
-    double x = pow(cells, 1.0 / db);
-    int32_t v = (int32_t)floor(x + 1e-9);
+    // mode 1: bin width ~ radius of the K-ball at mean density (kTunedMargin, kTunedMaxBins)
+    const int32_t db = d <= 3 ? d : (d == 4 ? 3 : 5);
+    const double unit_ball = pow(M_PI, 0.5 * d) / tgamma(0.5 * d + 1.0);
+    const double margin = d >= 6 ? kTunedMarginHighD : kTunedMargin;
+    double x = n_elems > 0 ? margin * pow(n_elems * unit_ball / (double)k, 1.0 / d) : 1.0;
+    int32_t v = (int32_t)floor(x + 0.5);
     v = v < 1 ? 1 : (v > kTunedMaxBins ? kTunedMaxBins : v);
     while (pow((double)v, db) * n_segments > (double)FG_MAX_TOTAL_BINS && v > 1) --v;
     *n_bins = v;

@@ -3,10 +3,11 @@
 //
 // Stages, all enqueued on one stream:
 //   prepare   zero the bin counters, reset the bounding-box keys
-//   bbox      per row split, min/max of the first d_bin coordinates (wave reduction + one
-//             atomic per wave and dimension on an order-preserving integer key)
+//   bbox      per row split, min/max of the first d_bin coordinates (register, wave and block
+//             reduction, one atomic pair per block and dimension on an order-preserving key)
 //   geometry  per (row split, dim): lower edge, bins per unit length, bin width, rounding slack
-//   assign    flat bin of every point + its arrival rank inside the bin (returning atomic)
+//   assign    flat bin of every point + its arrival rank inside the bin (LDS-privatised
+//             histogram per block, one returning global atomic per distinct bin and block)
 //   scan      exclusive prefix over the counters (partials / tops / apply)
 //   scatter   sorted position = bounds[bin] + rank: write perm and the bin-ordered SoA coords
 #include "fg_internal.hpp"
@@ -152,24 +153,65 @@ k_geometry(const uint32_t* __restrict__ bbox_keys, int32_t n_keys, int32_t n_bin
     g[0] = lo; g[1] = inv_w; g[2] = w; g[3] = slack;
 }
 
+// Bin of every point and its arrival rank inside the bin.  The rank comes from an atomic add on
+// the bin's counter; atomics on one address serialise, and skewed data put a large share of all
+// points into a few bins.  So a block first counts its kAssignChunk points per bin in an
+// LDS-privatised histogram (an open-addressing table keyed by bin, LDS atomics give the rank
+// inside the block), then adds each distinct bin's block total to the global counter once, and
+// finally hands every point the block's base plus its local rank.  A point that finds no table
+// slot within kAssignProbes probes takes the global atomic directly.
+constexpr int kAssignItems = 4;
+constexpr int kAssignChunk = kBlock * kAssignItems;
+constexpr int kAssignSlots = 2048;
+constexpr int kAssignProbes = 8;
+
 template <int DB>
 __global__ void __launch_bounds__(kBlock)
 k_assign(const float* __restrict__ coords, const int32_t* __restrict__ row_splits, int32_t n, int32_t d,
          int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, const float* __restrict__ geom,
          int32_t* __restrict__ bin_idx, int32_t* __restrict__ rank, int32_t* __restrict__ counters)
 {
-    int32_t i = blockIdx.x * kBlock + threadIdx.x;
-    if (i >= n) return;
-    int32_t s = segment_of(row_splits, n_segments, i);
-    const float* p = coords + (int64_t)i * d;
-    const float* g = geom + (int64_t)s * DB * kGeomStride;
-    int32_t flat = 0;
+    __shared__ int32_t keys[kAssignSlots];
+    __shared__ int32_t cnts[kAssignSlots];     // block-local population, then the block's base in the bin
+    for (int i = threadIdx.x; i < kAssignSlots; i += kBlock) { keys[i] = -1; cnts[i] = 0; }
+    __syncthreads();
+    int32_t flat[kAssignItems], slot[kAssignItems], local[kAssignItems];
 #pragma unroll
-    for (int c = 0; c < DB; ++c)
-        flat = flat * n_bins + cell_of(p[c], g[c * kGeomStride + 0], g[c * kGeomStride + 1], n_bins);
-    flat += s * cells_per_segment;
-    bin_idx[i] = flat;
-    rank[i] = atomicAdd(&counters[flat], 1);
+    for (int it = 0; it < kAssignItems; ++it) {
+        const int64_t i = (int64_t)blockIdx.x * kAssignChunk + it * kBlock + threadIdx.x;
+        flat[it] = -1; slot[it] = -1; local[it] = 0;
+        if (i >= n) continue;
+        const int32_t s = segment_of(row_splits, n_segments, (int32_t)i);
+        const float* p = coords + i * d;
+        const float* g = geom + (int64_t)s * DB * kGeomStride;
+        int32_t f = 0;
+#pragma unroll
+        for (int c = 0; c < DB; ++c)
+            f = f * n_bins + cell_of(p[c], g[c * kGeomStride + 0], g[c * kGeomStride + 1], n_bins);
+        f += s * cells_per_segment;
+        flat[it] = f;
+        bin_idx[i] = f;
+        uint32_t h = ((uint32_t)f * 2654435761u) >> 21;              // 11 bits
+#pragma unroll 1
+        for (int probe = 0; probe < kAssignProbes; ++probe) {
+            const int32_t prev = atomicCAS(&keys[h], -1, f);
+            if (prev == -1 || prev == f) { slot[it] = (int32_t)h; local[it] = atomicAdd(&cnts[h], 1); break; }
+            h = (h + 1) & (kAssignSlots - 1);
+        }
+        if (slot[it] < 0) local[it] = atomicAdd(&counters[f], 1);   // no slot: straight to memory
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kAssignSlots; i += kBlock) {
+        const int32_t f = keys[i];
+        if (f >= 0) cnts[i] = atomicAdd(&counters[f], cnts[i]);      // block total in, block base out
+    }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kAssignItems; ++it) {
+        const int64_t i = (int64_t)blockIdx.x * kAssignChunk + it * kBlock + threadIdx.x;
+        if (i >= n) continue;
+        rank[i] = slot[it] >= 0 ? cnts[slot[it]] + local[it] : local[it];
+    }
 }
 
 // ---- exclusive scan over the counters, in place: counters[b] -> first sorted position of bin b.
@@ -276,13 +318,12 @@ static void launch_bbox_assign(bool assign, const float* coords, const int32_t* 
                                const float* geom, int32_t* bin_idx, int32_t* rank, int32_t* counters,
                                hipStream_t stream)
 {
-    int grid = (n + kBlock - 1) / kBlock;
     if (!assign)
         hipLaunchKernelGGL(k_bbox<DB>, dim3((n + kBboxChunk - 1) / kBboxChunk), dim3(kBlock), 0, stream, coords,
                            row_splits, n, d, n_segments, bbox_keys);
     else
-        hipLaunchKernelGGL(k_assign<DB>, dim3(grid), dim3(kBlock), 0, stream, coords, row_splits, n, d, n_segments,
-                           n_bins, cells_per_segment, geom, bin_idx, rank, counters);
+        hipLaunchKernelGGL(k_assign<DB>, dim3((n + kAssignChunk - 1) / kAssignChunk), dim3(kBlock), 0, stream, coords,
+                           row_splits, n, d, n_segments, n_bins, cells_per_segment, geom, bin_idx, rank, counters);
 }
 
 template <int D>
