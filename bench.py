@@ -54,7 +54,7 @@ def main() -> int:
     ap.add_argument("--n-bins", type=int, default=0)
     ap.add_argument("--d-bin", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rows", type=int, default=40000)
+    ap.add_argument("--cpu-rows", type=int, default=100000)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (segments are independent and would "

@@ -89,7 +89,8 @@ typedef struct {
                                   shell walk for every query (slower; same result; kept for cross-checking) */
     int32_t defer_lanes;       /* tuning knob of the tile kernel, 0..64 (set by fg_bin_points): after shell 1 a
                                   wavefront goes on to the next shell only while more than this many of its 64
-                                  queries are unfinished; the rest go to the list kernel.  Result-neutral. */
+                                  queries are unfinished (and its lanes have been evenly loaded so far); the
+                                  rest go to the list kernel.  Result-neutral. */
 } fg_binning;
 
 /* Spatial partition + counting sort (Section 3: "points are sorted by bin assignments and

@@ -38,16 +38,18 @@ constexpr size_t kAlign = 256;
 // (3 bins per dimension) is enough for most queries, i.e. when the bin width is about the
 // radius r_K of the ball that holds K points at the mean density of a row split:
 //   r_K = extent * (K / (n_elems * V_d))^(1/d),  V_d = volume of the unit ball in d dimensions,
-// so bins per dimension = kTunedMargin * (n_elems * V_d / K)^(1/d).  Same functional form as
+// so bins per dimension = margin * (n_elems * V_d / K)^(1/d).  Same functional form as
 // the paper's heuristic (a power 1/d of n_elems / K), with the constant 32 replaced by V_d and
 // the exponent taken over all d coordinates because the distance is.  Binning dimensions: all of
 // them up to 3; the first 3 for d = 4; the first 5 from d = 5 on (measured on uniform data).
-// From d = 6 on a cube of 3 bins per side wastes most of its volume outside the ball, and bins
-// of about 0.6 r_K searched two shells deep (with box pruning) measured faster.
-constexpr double kTunedMargin = 0.9;
-constexpr double kTunedMarginHighD = 1.6;
+// From d = 6 on a cube of 3 bins per side wastes most of its volume outside the ball, and
+// smaller bins searched two shells deep (with box pruning) measured faster.
+// Margins measured on uniform data (1e5..1e6 points, K = 10..100) and on the clustered
+// configurations: the best bin width is ~0.8 r_K for d <= 3, ~0.65 r_K for d = 4 (only 3 of 4
+// dimensions are binned), ~1.1 r_K for d = 5, ~0.6 r_K beyond.
+constexpr double kTunedMarginByDim[11] = {0, 0, 1.2, 1.2, 1.5, 0.9, 1.6, 1.6, 1.6, 1.6, 1.6};
 constexpr int32_t kTunedMaxBins = 1024;
-constexpr int32_t kDefaultDeferLanes = 63;
+constexpr int32_t kDefaultDeferLanes = 24;
 constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -153,10 +155,10 @@ fg_status fg_auto_n_bins(int64_t n, int32_t n_segments, int32_t k, int32_t d, in
         *d_bin = db;
         return FG_OK;
     }
-    // mode 1: bin width ~ radius of the K-ball at mean density (kTunedMargin, kTunedMaxBins)
+    // mode 1: bin width ~ radius of the K-ball at mean density (kTunedMarginByDim, kTunedMaxBins)
     const int32_t db = d <= 3 ? d : (d == 4 ? 3 : 5);
     const double unit_ball = pow(M_PI, 0.5 * d) / tgamma(0.5 * d + 1.0);
-    const double margin = d >= 6 ? kTunedMarginHighD : kTunedMargin;
+    const double margin = kTunedMarginByDim[d];
     double x = n_elems > 0 ? margin * pow(n_elems * unit_ball / (double)k, 1.0 / d) : 1.0;
     int32_t v = (int32_t)floor(x + 0.5);
     v = v < 1 ? 1 : (v > kTunedMaxBins ? kTunedMaxBins : v);

@@ -63,6 +63,8 @@ k_query_tile_sorted(QueryArgs a)
 #pragma unroll
     for (int i = 0; i < KC; ++i) best[i] = (i < KC - cap) ? 0ull : ~0ull;
     int32_t cnt = 0, cand = 0;
+    int32_t useful = 0;   // candidates this lane evaluated
+    int32_t passes = 0;   // scan passes of the wave (kUnroll lane slots each)
 
     auto absorb = [&]() {
         uint64_t pend[kPend];
@@ -183,6 +185,7 @@ k_query_tile_sorted(QueryArgs a)
                 const int32_t top = base + cnt_pts;
                 int32_t q = a1 > base ? a1 : base, e = b1 < top ? b1 : top;
                 int32_t q2 = a2 > base ? a2 : base, e2 = b2 < top ? b2 : top;
+                useful += (e > q ? e - q : 0) + (e2 > q2 ? e2 - q2 : 0);
                 for (;;) {
                     if (q >= e && q2 < e2) { q = q2; e = e2; q2 = e2; }
                     const int32_t rem = e - q;
@@ -216,6 +219,7 @@ k_query_tile_sorted(QueryArgs a)
                         }
                     }
                     q += kUnroll;
+                    ++passes;
 #ifdef FG_TILE_PROF
                     ++n_iter;
                     if (__any(cnt > kPend - kUnroll)) { long long t2 = clock64(); absorb(); t_absorb += clock64() - t2; ++n_absorb; }
@@ -232,7 +236,15 @@ k_query_tile_sorted(QueryArgs a)
         if (active && s.certified(R)) active = false;
         const int32_t n_active = __popcll(__ballot(active));
         if (n_active == 0) break;
-        if (R >= 1 && n_active <= a.defer_lanes) break;
+        if (R >= 1) {
+            // Go on to the next shell in this wave only if that is efficient: enough lanes still
+            // searching, and the lanes so far evenly loaded (candidates actually evaluated vs lane
+            // slots spent).  An uneven tile (sparse lanes next to a dense cluster) keeps 64 lanes
+            // waiting for a few; its unfinished queries are cheaper one per wavefront.
+            if (n_active <= a.defer_lanes) break;
+            const int32_t spent = passes * kUnroll;
+            if (wave_sum_i32(useful) * 5 < spent * kQueryBlock * 2) break;     // below 40 % lane use
+        }
     }
 
     // unfinished lanes go to the work list (wave-aggregated append)
