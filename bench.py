@@ -127,7 +127,8 @@ def main() -> int:
     total_bins = binning.n_segments * binning.cells_per_segment
     algo_bytes = n * (k * 8 + d * 4 + 4) + (total_bins + 1) * 4
     achieved = algo_bytes / (ms_query * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "query", "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
+    roofline = {"bound": "hbm", "kernel": "query stage = k_query_tile_sorted + k_query_list_wave (two launches)",
+                "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
                 "traffic": _traffic_from_profiles("query_kernel_%s_traffic.txt" % w.name.split("_")[0]),
                 "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": round(ms_query, 4)}
