@@ -45,9 +45,11 @@ constexpr size_t kAlign = 256;
 // From d = 6 on a cube of 3 bins per side wastes most of its volume outside the ball, and
 // smaller bins searched two shells deep (with box pruning) measured faster.
 // Margins measured on uniform data (1e5..1e6 points, K = 10..100) and on the clustered
-// configurations: the best bin width is ~0.8 r_K for d <= 3, ~0.65 r_K for d = 4 (only 3 of 4
-// dimensions are binned), ~1.1 r_K for d = 5, ~0.6 r_K beyond.
-constexpr double kTunedMarginByDim[11] = {0, 0, 1.2, 1.2, 1.5, 0.9, 1.6, 1.6, 1.6, 1.6, 1.6};
+// configurations.  For d <= 3 and d = 5 the bin width is ~1.1 r_K: finer grids are as fast or
+// faster on clustered data and for K >= 40, but for small K a large share of the queries then
+// needs a second shell and leaves the tile kernel.  d = 4 (3 of 4 dimensions binned) ~0.8 r_K,
+// d >= 6 ~0.6 r_K.
+constexpr double kTunedMarginByDim[11] = {0, 0, 0.9, 0.9, 1.2, 0.9, 1.6, 1.6, 1.6, 1.6, 1.6};
 constexpr int32_t kTunedMaxBins = 1024;
 constexpr int32_t kDefaultDeferLanes = 24;
 constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk

@@ -23,6 +23,11 @@
 
 namespace fg {
 
+#ifndef FG_TILE_WAVES32
+#define FG_TILE_WAVES32 3
+#endif
+// waves per SIMD the register allocator aims at: the sorted list alone takes 2*KC registers
+template <int KC> constexpr int tile_waves() { return KC <= 16 ? 4 : (KC == 32 ? FG_TILE_WAVES32 : 2); }
 constexpr int kPend = 16;   // pending keys per lane between two merges
 struct Ranges { int32_t a1, b1, a2, b2; };
 
@@ -32,7 +37,7 @@ constexpr int kUnroll = 4;  // candidates per lane per pass of the scan loop (in
 template <int D> constexpr int stage_vecs() { return (D + 1 + 3) / 4; }
 
 template <int D, int DB, int KC, bool COUNT>
-__global__ void __launch_bounds__(kQueryBlock)
+__global__ void __launch_bounds__(kQueryBlock) __attribute__((amdgpu_waves_per_eu(tile_waves<KC>(), tile_waves<KC>())))
 k_query_tile_sorted(QueryArgs a)
 {
     // LDS: [pending kPend x 64 keys][stage (D+1) x kStageChunk words]; re-used at the end as
