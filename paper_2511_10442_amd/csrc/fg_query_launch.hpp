@@ -33,6 +33,9 @@ static hipError_t launch_query_impl(const QueryArgs& a, hipStream_t stream)
     } else if (cap <= 32) {
         const size_t lds = tile_sorted_lds_bytes<32, D>();
         hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 32, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
+    } else if (cap <= 48) {
+        const size_t lds = tile_sorted_lds_bytes<48, D>();
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 48, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     } else if (cap <= 64) {
         const size_t lds = tile_sorted_lds_bytes<64, D>();
         hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 64, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);

@@ -14,7 +14,7 @@
 //     at the end of every shell, all lanes absorb their pending keys into the sorted register
 //     list with a fixed merging network (no data-dependent addressing, no LDS round trips);
 //   * keys are 64-bit (distance bits << 32 | original index); slots beyond K-1 are pinned with
-//     zero keys so that the last register is always the (K-1)-th best;
+//     zero keys so that the last register is always the (K-1)-th best (list sizes 16/32/48/64);
 //   * finished rows leave through LDS so that each output row is written as contiguous bytes;
 //   * lanes still uncertified when few are left are handed to the list kernel.
 #pragma once

@@ -51,7 +51,9 @@ __host__ __device__ __forceinline__ void net_merge(uint64_t (&v)[M])
     }
 }
 
-// best[0..KC) ascending, pend[0..P) ascending, P <= KC:
+constexpr int next_pow2(int v) { int p = 1; while (p < v) p <<= 1; return p; }
+
+// best[0..KC) ascending, pend[0..P) ascending, P <= KC, P a power of two, KC a multiple of P:
 // afterwards best holds the KC smallest of the union, ascending.
 template <int KC, int P>
 __host__ __device__ __forceinline__ void net_absorb(uint64_t (&best)[KC], const uint64_t (&pend)[P])
@@ -66,13 +68,19 @@ __host__ __device__ __forceinline__ void net_absorb(uint64_t (&best)[KC], const 
         net_merge<KC, 0>(best);
     } else {
         net_merge<P, KC - P>(best);          // tail ascending
-        // head ascending + reversed tail is bitonic: merge on a renamed copy
-        uint64_t w[KC];
+        // head ascending + reversed tail is bitonic: merge on a renamed copy.  When KC is not a
+        // power of two the copy is padded in the middle with all-ones keys up to the next power
+        // of two (ascending head, plateau of maxima, descending tail is still bitonic); the
+        // padding is a compile-time constant, so every comparator that meets it folds away.
+        constexpr int N = next_pow2(KC);
+        uint64_t w[N];
 #pragma unroll
         for (int i = 0; i < KC - P; ++i) w[i] = best[i];
 #pragma unroll
-        for (int i = 0; i < P; ++i) w[KC - P + i] = best[KC - 1 - i];
-        net_merge<KC, 0>(w);
+        for (int i = KC - P; i < N - P; ++i) w[i] = ~0ull;
+#pragma unroll
+        for (int i = 0; i < P; ++i) w[N - P + i] = best[KC - 1 - i];
+        net_merge<N, 0>(w);
 #pragma unroll
         for (int i = 0; i < KC; ++i) best[i] = w[i];
     }

@@ -46,7 +46,8 @@ int main()
     int bad = 0;
     bad |= check_sort<2>(rng) | check_sort<4>(rng) | check_sort<8>(rng) | check_sort<16>(rng) | check_sort<32>(rng) | check_sort<64>(rng);
     bad |= check_absorb<16, 16>(rng) | check_absorb<32, 16>(rng) | check_absorb<64, 16>(rng) | check_absorb<32, 8>(rng) |
-           check_absorb<64, 32>(rng) | check_absorb<16, 8>(rng) | check_absorb<128, 16>(rng);
+           check_absorb<64, 32>(rng) | check_absorb<16, 8>(rng) | check_absorb<128, 16>(rng) |
+           check_absorb<48, 16>(rng) | check_absorb<24, 8>(rng) | check_absorb<96, 16>(rng) | check_absorb<80, 16>(rng);
     std::printf(bad ? "FAIL\n" : "OK\n");
     return bad;
 }
