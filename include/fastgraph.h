@@ -85,6 +85,8 @@ typedef struct {
     int32_t d_bin;             /* binning dimensions actually used (the first d_bin coordinates) */
     int32_t* work_list;        /* [n]  scratch of the query stage: queries handed from the tile kernel to the list kernel */
     int32_t* work_count;       /* [1]  scratch of the query stage */
+    const int32_t* dir;        /* [n] direction flags in ORIGINAL row order for the query stage, or NULL (set to NULL
+                                  by fg_bin_points; see fg_binned_select_knn_dir) */
     int32_t query_algo;        /* 0 (set by fg_bin_points): tile kernel + list kernel; 1: the one-lane-per-query
                                   shell walk for every query (slower; same result; kept for cross-checking) */
     int32_t defer_lanes;       /* tuning knob of the tile kernel, 0..64 (set by fg_bin_points): after shell 1 a
@@ -121,6 +123,18 @@ fg_status fg_binned_select_knn(const float* coords, const int32_t* row_splits, i
                                int32_t d, int32_t n_segments, int32_t k, int32_t n_bins,
                                int32_t d_bin, int32_t* out_idx, float* out_d2,
                                void* workspace, size_t workspace_bytes, void* stream);
+
+/* Direction-flag variant (Algorithm 2, inputs useDir and dir[]): dir [n] int32, one flag per point:
+ *   0  the point can be a neighbour but issues no query
+ *   1  the point queries but is nobody's neighbour
+ *   2  neither
+ *   any other value: both (the plain behaviour)
+ * The row of a point that issues no query is all padding (index -1, distance 0, slot 0 included).
+ * A querying point is its own slot 0 whatever its flag.  dir == NULL: same as fg_binned_select_knn. */
+fg_status fg_binned_select_knn_dir(const float* coords, const int32_t* row_splits, const int32_t* dir,
+                                   int64_t n, int32_t d, int32_t n_segments, int32_t k, int32_t n_bins,
+                                   int32_t d_bin, int32_t* out_idx, float* out_d2,
+                                   void* workspace, size_t workspace_bytes, void* stream);
 
 /* Same as fg_binned_select_knn, and additionally writes, per row, the number of candidate
  * squared distances evaluated for it (Algorithm 2's inner loop trip count) into

@@ -46,10 +46,10 @@ def _load():
         f32p = ctypes.POINTER(ctypes.c_float)
         f64p = ctypes.POINTER(ctypes.c_double)
         lib.oracle_knn.restype = ctypes.c_int
-        lib.oracle_knn.argtypes = [f32p, i32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+        lib.oracle_knn.argtypes = [f32p, i32p, i32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                    ctypes.c_int, i32p, f32p, ctypes.c_int]
         lib.oracle_knn_rows.restype = ctypes.c_int
-        lib.oracle_knn_rows.argtypes = [f32p, i32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
+        lib.oracle_knn_rows.argtypes = [f32p, i32p, i32p, ctypes.c_int64, ctypes.c_int, ctypes.c_int,
                                         ctypes.c_int, i64p, ctypes.c_int64, i32p, f32p,
                                         ctypes.c_int]
         lib.oracle_knn_backward.restype = ctypes.c_int
@@ -77,13 +77,24 @@ def num_threads() -> int:
     return int(_load().oracle_num_threads())
 
 
-def knn(coords, row_splits, k: int, n_threads: int = 0):
-    """Exact kNN graph of every row: (idx int32 [n,k], d2 float32 [n,k])."""
+def _dir_ptr(direction, n):
+    if direction is None:
+        return None, None
+    direction = np.ascontiguousarray(direction, dtype=np.int32)
+    assert direction.shape == (n,)
+    return direction, _ptr(direction, ctypes.c_int32)
+
+
+def knn(coords, row_splits, k: int, n_threads: int = 0, direction=None):
+    """Exact kNN graph of every row: (idx int32 [n,k], d2 float32 [n,k]).
+    direction: optional [n] flags of Algorithm 2 (0: neighbour only, 1: query only, 2: neither,
+    anything else: both)."""
     coords, row_splits = _check_inputs(coords, row_splits)
     n, d = coords.shape
+    direction, dptr = _dir_ptr(direction, n)
     idx = np.empty((n, k), dtype=np.int32)
     d2 = np.empty((n, k), dtype=np.float32)
-    rc = _load().oracle_knn(_ptr(coords, ctypes.c_float), _ptr(row_splits, ctypes.c_int32),
+    rc = _load().oracle_knn(_ptr(coords, ctypes.c_float), _ptr(row_splits, ctypes.c_int32), dptr,
                             n, d, row_splits.shape[0] - 1, k,
                             _ptr(idx, ctypes.c_int32), _ptr(d2, ctypes.c_float), n_threads)
     if rc != 0:
@@ -91,14 +102,15 @@ def knn(coords, row_splits, k: int, n_threads: int = 0):
     return idx, d2
 
 
-def knn_rows(coords, row_splits, k: int, rows, n_threads: int = 0):
+def knn_rows(coords, row_splits, k: int, rows, n_threads: int = 0, direction=None):
     """Exact kNN of the selected query rows only: ([len(rows),k], [len(rows),k])."""
     coords, row_splits = _check_inputs(coords, row_splits)
     rows = np.ascontiguousarray(rows, dtype=np.int64)
     n, d = coords.shape
+    direction, dptr = _dir_ptr(direction, n)
     idx = np.empty((rows.shape[0], k), dtype=np.int32)
     d2 = np.empty((rows.shape[0], k), dtype=np.float32)
-    rc = _load().oracle_knn_rows(_ptr(coords, ctypes.c_float), _ptr(row_splits, ctypes.c_int32),
+    rc = _load().oracle_knn_rows(_ptr(coords, ctypes.c_float), _ptr(row_splits, ctypes.c_int32), dptr,
                                  n, d, row_splits.shape[0] - 1, k,
                                  _ptr(rows, ctypes.c_int64), rows.shape[0],
                                  _ptr(idx, ctypes.c_int32), _ptr(d2, ctypes.c_float), n_threads)

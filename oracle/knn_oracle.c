@@ -21,6 +21,11 @@
  *   - a row split with m < K points leaves slots m..K-1 as (index -1, distance 0); -1 is the
  *     padding value the paper's package uses elsewhere (Algorithm 3).
  *
+ * Direction flags (Algorithm 2, inputs useDir and dir[]): with flags given, a point whose flag
+ * is 0 or 2 issues no query (its output row is all padding: index -1, distance 0, slot 0
+ * included), and a point whose flag is 1 or 2 is never anybody's neighbour; any other value
+ * means both roles.  A querying point is still its own slot 0 whatever its flag.
+ *
  * Backward (Section 3, last paragraph: gradients of the returned distances): the derivative
  * of d2(v,u) = sum_c (x[v][c]-x[u][c])^2 with respect to the coordinates, accumulated in
  * double precision.
@@ -62,7 +67,7 @@ static inline int pair_less(float d2a, int32_t ia, float d2b, int32_t ib)
 }
 
 /* One query: scan its row split [s,e), keep the K-1 best others sorted in best_*[0..filled). */
-static void one_query(const float* coords, int d, int64_t s, int64_t e, int64_t v, int k,
+static void one_query(const float* coords, const int32_t* dir, int d, int64_t s, int64_t e, int64_t v, int k,
                       int32_t* out_idx, float* out_d2)
 {
     float buf[ORACLE_BLOCK];
@@ -72,9 +77,9 @@ static void one_query(const float* coords, int d, int64_t s, int64_t e, int64_t 
     float* bd = out_d2 + 1;
     const float* q = coords + v * (int64_t)d;
 
+    for (int j = 0; j < k; ++j) { out_idx[j] = -1; out_d2[j] = 0.0f; }
+    if (dir && (dir[v] == 0 || dir[v] == 2)) return;      /* not a query */
     out_idx[0] = (int32_t)v;
-    out_d2[0] = 0.0f;
-    for (int j = 1; j < k; ++j) { out_idx[j] = -1; out_d2[j] = 0.0f; }
     if (cap == 0) return;
 
     for (int64_t u0 = s; u0 < e; u0 += ORACLE_BLOCK) {
@@ -83,6 +88,7 @@ static void one_query(const float* coords, int d, int64_t s, int64_t e, int64_t 
         for (int i = 0; i < m; ++i) {
             int64_t u = u0 + i;
             if (u == v) continue;
+            if (dir && (dir[u] == 1 || dir[u] == 2)) continue;   /* not a neighbour */
             float d2 = buf[i];
             if (filled == cap && !pair_less(d2, (int32_t)u, bd[cap - 1], bi[cap - 1])) continue;
             /* insertion into the sorted list */
@@ -107,8 +113,8 @@ static int64_t find_segment(const int32_t* row_splits, int n_segments, int64_t v
     return -1;
 }
 
-/* Full graph.  out_idx/out_d2 are [n][k] row-major. Returns 0, or -1 on bad arguments. */
-int oracle_knn(const float* coords, const int32_t* row_splits, int64_t n, int d,
+/* Full graph.  dir: [n] direction flags or NULL.  out_idx/out_d2 are [n][k] row-major. Returns 0, or -1 on bad arguments. */
+int oracle_knn(const float* coords, const int32_t* row_splits, const int32_t* dir, int64_t n, int d,
                int n_segments, int k, int32_t* out_idx, float* out_d2, int n_threads)
 {
     if (!coords || !row_splits || !out_idx || !out_d2 || d < 1 || k < 1 || n_segments < 1) return -1;
@@ -121,13 +127,13 @@ int oracle_knn(const float* coords, const int32_t* row_splits, int64_t n, int d,
         if (e < b) return -1;
 #pragma omp parallel for schedule(dynamic, 64)
         for (int64_t v = b; v < e; ++v)
-            one_query(coords, d, b, e, v, k, out_idx + v * (int64_t)k, out_d2 + v * (int64_t)k);
+            one_query(coords, dir, d, b, e, v, k, out_idx + v * (int64_t)k, out_d2 + v * (int64_t)k);
     }
     return 0;
 }
 
 /* Selected rows only: out_idx/out_d2 are [n_rows][k], row i answering query rows[i]. */
-int oracle_knn_rows(const float* coords, const int32_t* row_splits, int64_t n, int d,
+int oracle_knn_rows(const float* coords, const int32_t* row_splits, const int32_t* dir, int64_t n, int d,
                     int n_segments, int k, const int64_t* rows, int64_t n_rows,
                     int32_t* out_idx, float* out_d2, int n_threads)
 {
@@ -142,7 +148,7 @@ int oracle_knn_rows(const float* coords, const int32_t* row_splits, int64_t n, i
         int64_t v = rows[i];
         int64_t s = (v >= 0 && v < n) ? find_segment(row_splits, n_segments, v) : -1;
         if (s < 0) { bad = 1; continue; }
-        one_query(coords, d, row_splits[s], row_splits[s + 1], v, k,
+        one_query(coords, dir, d, row_splits[s], row_splits[s + 1], v, k,
                   out_idx + i * (int64_t)k, out_d2 + i * (int64_t)k);
     }
     return bad ? -1 : 0;

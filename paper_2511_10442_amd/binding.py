@@ -23,7 +23,7 @@ FG_ERR_WORKSPACE = 4
 FG_ERR_LAUNCH = 5
 
 EXPORTS = ["fg_status_string", "fg_auto_n_bins", "fg_workspace_size", "fg_bin_points",
-           "fg_binned_select_knn", "fg_binned_select_knn_counted", "fg_query_binned",
+           "fg_binned_select_knn", "fg_binned_select_knn_dir", "fg_binned_select_knn_counted", "fg_query_binned",
            "fg_knn_backward"]
 
 
@@ -39,7 +39,7 @@ class _Binning(ctypes.Structure):
                 ("seg_geom", ctypes.c_void_p), ("soa_stride", ctypes.c_int64),
                 ("cells_per_segment", ctypes.c_int64), ("n_bins", ctypes.c_int32),
                 ("d_bin", ctypes.c_int32), ("work_list", ctypes.c_void_p),
-                ("work_count", ctypes.c_void_p), ("query_algo", ctypes.c_int32),
+                ("work_count", ctypes.c_void_p), ("dir", ctypes.c_void_p), ("query_algo", ctypes.c_int32),
                 ("defer_lanes", ctypes.c_int32)]
 
 
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
                                     ctypes.POINTER(_Binning), vp]
         L.fg_binned_select_knn.restype = ctypes.c_int
         L.fg_binned_select_knn.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.fg_binned_select_knn_dir.restype = ctypes.c_int
+        L.fg_binned_select_knn_dir.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
         L.fg_binned_select_knn_counted.restype = ctypes.c_int
         L.fg_binned_select_knn_counted.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp,
                                                    vp, sz, vp]
@@ -217,6 +219,29 @@ def fg_binned_select_knn(coords: torch.Tensor, row_splits: torch.Tensor, k: int,
     _check(lib().fg_binned_select_knn(_ptr(coords), _ptr(row_splits), n, d, s, k, n_bins, d_bin,
                                       _ptr(out_idx), _ptr(out_d2), _ptr(workspace),
                                       workspace.numel(), _stream()), "fg_binned_select_knn")
+    return out_idx, out_d2
+
+
+def fg_binned_select_knn_dir(coords: torch.Tensor, row_splits: torch.Tensor, direction: torch.Tensor, k: int,
+                             n_bins: int = 0, d_bin: int = 0, workspace: torch.Tensor | None = None,
+                             out_idx=None, out_d2=None):
+    """Direction-flag variant: direction [n] int32 (0 neighbour only, 1 query only, 2 neither, else both)."""
+    coords = _dev(coords, torch.float32, "coords")
+    row_splits = _dev(row_splits, torch.int32, "row_splits")
+    direction = _dev(direction, torch.int32, "direction")
+    n, d = coords.shape
+    if direction.numel() != n:
+        raise ValueError("direction must have one flag per point")
+    s = row_splits.numel() - 1
+    if workspace is None:
+        workspace = alloc_workspace(n, d, s, k, n_bins, d_bin, coords.device)
+    if out_idx is None:
+        out_idx = torch.empty((n, k), dtype=torch.int32, device=coords.device)
+    if out_d2 is None:
+        out_d2 = torch.empty((n, k), dtype=torch.float32, device=coords.device)
+    _check(lib().fg_binned_select_knn_dir(_ptr(coords), _ptr(row_splits), _ptr(direction), n, d, s, k, n_bins,
+                                          d_bin, _ptr(out_idx), _ptr(out_d2), _ptr(workspace),
+                                          workspace.numel(), _stream()), "fg_binned_select_knn_dir")
     return out_idx, out_d2
 
 

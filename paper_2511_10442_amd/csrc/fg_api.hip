@@ -207,6 +207,7 @@ fg_status fg_bin_points(const float* coords, const int32_t* row_splits, int64_t 
     view->d_bin = d_bin;
     view->work_list = (int32_t*)(ws + L.work_list);
     view->work_count = (int32_t*)(ws + L.work_count);
+    view->dir = nullptr;
     view->query_algo = 0;
     view->defer_lanes = kDefaultDeferLanes;
     if (n == 0) return FG_OK;
@@ -235,7 +236,7 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
         return FG_ERR_BAD_SHAPE;
     QueryArgs a;
     a.soa = view->sorted_soa; a.perm = view->perm; a.bounds = view->bin_bounds; a.geom = view->seg_geom;
-    a.row_splits = row_splits; a.out_idx = out_idx; a.out_d2 = out_d2; a.out_cand = out_candidates;
+    a.row_splits = row_splits; a.dir = view->dir; a.out_idx = out_idx; a.out_d2 = out_d2; a.out_cand = out_candidates;
     a.soa_stride = view->soa_stride; a.n = (int32_t)n; a.n_segments = n_segments; a.k = k;
     a.n_bins = view->n_bins; a.cells_per_segment = (int32_t)view->cells_per_segment;
     a.work_list = view->work_list; a.work_count = view->work_count; a.algo = view->query_algo == 1 ? 1 : 0;
@@ -244,7 +245,7 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }
 
-static fg_status knn_impl(const float* coords, const int32_t* row_splits, int64_t n, int32_t d, int32_t n_segments,
+static fg_status knn_impl(const float* coords, const int32_t* row_splits, const int32_t* dir, int64_t n, int32_t d, int32_t n_segments,
                           int32_t k, int32_t n_bins, int32_t d_bin, int32_t* out_idx, float* out_d2,
                           int32_t* out_candidates, void* workspace, size_t workspace_bytes, void* stream)
 {
@@ -256,6 +257,7 @@ static fg_status knn_impl(const float* coords, const int32_t* row_splits, int64_
     st = fg_bin_points(coords, row_splits, n, d, n_segments, k, n_bins, d_bin, workspace, workspace_bytes, &view,
                        stream);
     if (st != FG_OK) return st;
+    view.dir = dir;
     return fg_query_binned(&view, row_splits, n, d, n_segments, k, out_idx, out_d2, out_candidates, stream);
 }
 
@@ -264,7 +266,16 @@ fg_status fg_binned_select_knn(const float* coords, const int32_t* row_splits, i
                                int32_t d_bin, int32_t* out_idx, float* out_d2,
                                void* workspace, size_t workspace_bytes, void* stream)
 {
-    return knn_impl(coords, row_splits, n, d, n_segments, k, n_bins, d_bin, out_idx, out_d2, nullptr, workspace,
+    return knn_impl(coords, row_splits, nullptr, n, d, n_segments, k, n_bins, d_bin, out_idx, out_d2, nullptr, workspace,
+                    workspace_bytes, stream);
+}
+
+fg_status fg_binned_select_knn_dir(const float* coords, const int32_t* row_splits, const int32_t* dir,
+                                   int64_t n, int32_t d, int32_t n_segments, int32_t k, int32_t n_bins,
+                                   int32_t d_bin, int32_t* out_idx, float* out_d2,
+                                   void* workspace, size_t workspace_bytes, void* stream)
+{
+    return knn_impl(coords, row_splits, dir, n, d, n_segments, k, n_bins, d_bin, out_idx, out_d2, nullptr, workspace,
                     workspace_bytes, stream);
 }
 
@@ -275,7 +286,7 @@ fg_status fg_binned_select_knn_counted(const float* coords, const int32_t* row_s
                                        void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!out_candidates && n > 0) return FG_ERR_NULL;
-    return knn_impl(coords, row_splits, n, d, n_segments, k, n_bins, d_bin, out_idx, out_d2, out_candidates,
+    return knn_impl(coords, row_splits, nullptr, n, d, n_segments, k, n_bins, d_bin, out_idx, out_d2, out_candidates,
                     workspace, workspace_bytes, stream);
 }
 

@@ -15,6 +15,7 @@ struct QueryArgs {
     const int32_t* bounds;     // [S*T+1]
     const float* geom;         // [S][d_bin][4]
     const int32_t* row_splits; // [S+1]
+    const int32_t* dir;        // [n] direction flags in ORIGINAL row order, or nullptr
     int32_t* out_idx;          // [n][k]
     float* out_d2;             // [n][k]
     int32_t* out_cand;         // [n] or nullptr
@@ -43,6 +44,16 @@ hipError_t launch_query(const QueryArgs& a, int32_t d, int32_t d_bin, hipStream_
 // perm != nullptr: rows are taken in bin order and combined in LDS; nullptr: plain atomic scatter
 hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, const int32_t* perm,
                            int32_t n, int32_t d, int32_t k, float* grad_coords, hipStream_t stream);
+
+// Direction flags (paper Algorithm 2, useDir / dir[]): 0 or 2 = issues no query, 1 or 2 = is nobody's
+// neighbour, anything else = both roles.
+__device__ __forceinline__ bool dir_is_query(int32_t f) { return f != 0 && f != 2; }
+__device__ __forceinline__ bool dir_is_neighbour(int32_t f) { return f != 1 && f != 2; }
+
+// Key of an empty best-list slot: just above the bit pattern of +infinity, so every real key
+// (finite or infinite squared distance) is below it and every NaN squared distance is not.
+// Candidates excluded by a direction flag are staged with NaN coordinates and so can never be kept.
+constexpr uint64_t kEmptyKey = 0x7f800001ull << 32;
 
 // Segment of a (sorted or original) position: largest s with row_splits[s] <= p, skipping empty
 // segments by construction (row_splits[s+1] > p).

@@ -25,7 +25,7 @@ constexpr int kStageChunk = 256;                  // points staged through LDS p
 constexpr float kBoundShrink = 0.99999618530273f;  // 1 - 2^-18: covers fp32 rounding of d2 and of the bound
 
 // Per-lane geometry of one query: its coordinates, its bin, its row split's grid, and the
-// current k-th best key `tau` (all-ones until K-1 candidates have been kept).
+// current k-th best key `tau` (at or above kEmptyKey until K-1 candidates have been kept).
 template <int D, int DB>
 struct LaneGeom {
     float x[D];
@@ -39,7 +39,7 @@ struct LaneGeom {
     // true when no point of a box at squared lower-bound distance b2 can enter the best list
     __device__ __forceinline__ bool cannot_improve(float b2) const
     {
-        return tau != ~0ull && b2 > 1e-30f && tau_d2() < b2 * kBoundShrink;
+        return tau < kEmptyKey && b2 > 1e-30f && tau_d2() < b2 * kBoundShrink;
     }
 
     // lower bound (>= 0) on |x_c - y_c| for any point y whose bin index in dimension c is j = cc[c] + o
@@ -78,7 +78,7 @@ struct LaneGeom {
     __device__ __forceinline__ void init_geom(const QueryArgs& a, int32_t p)
     {
         n_bins = a.n_bins;
-        tau = ~0ull;
+        tau = kEmptyKey;
         const int32_t seg = segment_of(a.row_splits, a.n_segments, p);
         seg_cell0 = seg * a.cells_per_segment;
 #pragma unroll
@@ -106,6 +106,7 @@ struct ShellSearch : LaneGeom<D, DB> {
     const float* __restrict__ soa;
     const int32_t* __restrict__ perm;
     const int32_t* __restrict__ bounds;
+    const int32_t* __restrict__ dir;
     int64_t stride;
     int32_t self_pos, cap, filled, cand;
 #ifdef FG_DEBUG_SHELLS
@@ -165,7 +166,9 @@ struct ShellSearch : LaneGeom<D, DB> {
             if (COUNT) ++cand;
             uint32_t bits = __float_as_uint(d2);
             if (bits > (uint32_t)(tau >> 32)) continue;
-            uint64_t key = ((uint64_t)bits << 32) | (uint32_t)perm[q];
+            const int32_t row = perm[q];
+            if (dir && !dir_is_neighbour(dir[row])) continue;
+            uint64_t key = ((uint64_t)bits << 32) | (uint32_t)row;
             offer(key);
         }
     }
@@ -189,6 +192,7 @@ struct ShellSearch : LaneGeom<D, DB> {
             if (COUNT) ++cand;
             uint32_t bits = __float_as_uint(d2);
             if (bits > (uint32_t)(tau >> 32)) continue;
+            if (dir && !dir_is_neighbour(dir[stage_idx[i]])) continue;
             offer(((uint64_t)bits << 32) | (uint32_t)stage_idx[i]);
         }
     }
@@ -258,7 +262,7 @@ template <int D, int DB, bool COUNT>
 __device__ __forceinline__ void init_lane(ShellSearch<D, DB, COUNT>& s, const QueryArgs& a, int32_t p, uint64_t* heap)
 {
     s.heap = heap;
-    s.soa = a.soa; s.perm = a.perm; s.bounds = a.bounds; s.stride = a.soa_stride;
+    s.soa = a.soa; s.perm = a.perm; s.bounds = a.bounds; s.dir = a.dir; s.stride = a.soa_stride;
     s.self_pos = p; s.cap = a.k - 1; s.filled = 0; s.cand = 0;
     s.init_geom(a, p);
 }
@@ -271,7 +275,7 @@ __device__ __forceinline__ void write_row(ShellSearch<D, DB, COUNT>& s, const Qu
     const int32_t row = a.perm[p];
     int32_t* oi = a.out_idx + (int64_t)row * a.k;
     float* od = a.out_d2 + (int64_t)row * a.k;
-    oi[0] = row;
+    oi[0] = (a.dir && !dir_is_query(a.dir[row])) ? -1 : row;    // a point that asks nothing gets an all-padding row
     od[0] = 0.0f;
     for (int32_t j = 0; j < s.cap; ++j) {
         if (j < s.filled) {
@@ -350,7 +354,7 @@ k_query_tile(QueryArgs a)
     ShellSearch<D, DB, COUNT> s;
     init_lane(s, a, valid ? p : a.n - 1, lds64 + lane);   // dead lanes shadow the last point, never scan or write
     s.self_pos = p;
-    bool active = valid && cap > 0;
+    bool active = valid && cap > 0 && !(a.dir && !dir_is_query(a.dir[a.perm[valid ? p : a.n - 1]]));
 
     for (int32_t R = 0;; ++R) {   // ends at the latest at R = n_bins - 1, when every lane's cube covers its grid
         const int32_t side = 2 * R + 1;
@@ -465,7 +469,7 @@ k_query_shell(QueryArgs a)
     if (p >= a.n) return;
     ShellSearch<D, DB, COUNT> s;
     init_lane(s, a, p, lds64 + threadIdx.x);
-    s.run();
+    if (!(a.dir && !dir_is_query(a.dir[a.perm[p]]))) s.run();
     write_row(s, a, p, false);
 }
 

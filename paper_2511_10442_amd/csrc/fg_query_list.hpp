@@ -74,12 +74,12 @@ k_query_list_wave(QueryArgs a)
         const int32_t p = a.work_list[item];
         LaneGeom<D, DB> s;                          // identical in every lane
         s.init_geom(a, p);
-        uint64_t best = lane < kQueryBlock - cap ? 0ull : ~0ull;   // ascending by lane; low lanes pinned
+        uint64_t best = lane < kQueryBlock - cap ? 0ull : kEmptyKey;   // ascending by lane; low lanes pinned
         int32_t npend = 0, cand = 0;
 
         auto absorb64 = [&]() {                     // merges pend[0..min(npend,64)) into the best list
             const int32_t take = npend < kQueryBlock ? npend : kQueryBlock;
-            uint64_t v = lane < take ? pend[lane] : ~0ull;
+            uint64_t v = lane < take ? pend[lane] : kEmptyKey;
             uint64_t rest = (lane + kQueryBlock < npend) ? pend[lane + kQueryBlock] : 0ull;
             __syncthreads();
             if (lane + kQueryBlock < npend) pend[lane] = rest;
@@ -179,8 +179,9 @@ k_query_list_wave(QueryArgs a)
                         diff = s.x[c] - a.soa[(int64_t)c * a.soa_stride + q];
                         d2 = d2 + diff * diff;
                     }
-                    const bool live = in && q != p;
-                    const uint64_t key = ((uint64_t)__float_as_uint(d2) << 32) | (uint32_t)a.perm[q];
+                    const int32_t src = a.perm[q];
+                    const bool live = in && q != p && !(a.dir && !dir_is_neighbour(a.dir[src]));
+                    const uint64_t key = ((uint64_t)__float_as_uint(d2) << 32) | (uint32_t)src;
                     const bool acc = live && key < s.tau;
                     if (COUNT) cand += __popcll(__ballot(live));
                     const uint64_t m = __ballot(acc);
@@ -203,7 +204,7 @@ k_query_list_wave(QueryArgs a)
         if (lane == 0) { oi[0] = row; od[0] = 0.0f; }
         if (lane >= kQueryBlock - cap) {
             const int32_t j = lane - (kQueryBlock - cap) + 1;
-            const bool real = best != ~0ull;
+            const bool real = best < kEmptyKey;
             oi[j] = real ? (int32_t)(uint32_t)best : -1;
             od[j] = real ? __uint_as_float((uint32_t)(best >> 32)) : 0.0f;
         }

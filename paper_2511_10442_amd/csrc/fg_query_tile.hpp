@@ -53,7 +53,9 @@ k_query_tile_sorted(QueryArgs a)
     const bool valid = p < a.n;
     LaneGeom<D, DB> s;
     s.init_geom(a, valid ? p : a.n - 1);  // dead lanes shadow the last point, never scan or write
-    bool active = valid && cap > 0;
+    const int32_t my_row = a.perm[valid ? p : a.n - 1];
+    const bool asks = !(a.dir && !dir_is_query(a.dir[my_row]));   // direction flag: does this point query at all
+    bool active = valid && cap > 0 && asks;
 
 #ifdef FG_TILE_PROF
     long long t_all = clock64(), t_setup = 0, t_stage = 0, t_scan = 0, t_absorb = 0, t_out = 0, tt;
@@ -66,7 +68,7 @@ k_query_tile_sorted(QueryArgs a)
 #endif
     uint64_t best[KC];
 #pragma unroll
-    for (int i = 0; i < KC; ++i) best[i] = (i < KC - cap) ? 0ull : ~0ull;
+    for (int i = 0; i < KC; ++i) best[i] = (i < KC - cap) ? 0ull : kEmptyKey;
     int32_t cnt = 0, cand = 0;
     int32_t useful = 0;   // candidates this lane evaluated
     int32_t passes = 0;   // scan passes of the wave (kUnroll lane slots each)
@@ -76,7 +78,7 @@ k_query_tile_sorted(QueryArgs a)
 #pragma unroll
         for (int i = 0; i < kPend; ++i) {
             const uint64_t v = pend_lds[i * kQueryBlock];
-            pend[i] = i < cnt ? v : ~0ull;
+            pend[i] = i < cnt ? v : kEmptyKey;
         }
         net_sort<kPend>(pend);
         net_absorb<KC, kPend>(best, pend);
@@ -179,7 +181,12 @@ k_query_tile_sorted(QueryArgs a)
                     for (int c = 0; c < NV * 4; ++c) w[c] = 0.0f;
 #pragma unroll
                     for (int c = 0; c < D; ++c) w[c] = a.soa[(int64_t)c * a.soa_stride + base + i];
-                    w[D] = __int_as_float(a.perm[base + i]);
+                    const int32_t src = a.perm[base + i];
+                    w[D] = __int_as_float(src);
+                    if (a.dir && !dir_is_neighbour(a.dir[src])) {          // never a neighbour: poison its coordinates
+#pragma unroll
+                        for (int c = 0; c < D; ++c) w[c] = __uint_as_float(0x7fc00000u);
+                    }
 #pragma unroll
                     for (int v = 0; v < NV; ++v) stage[i * NV + v] = make_float4(w[4 * v], w[4 * v + 1], w[4 * v + 2], w[4 * v + 3]);
                 }
@@ -268,8 +275,7 @@ k_query_tile_sorted(QueryArgs a)
     // two passes (indices, then distances) so the transposition needs KC x 64 words, not keys
     int32_t* rows_lds = reinterpret_cast<int32_t*>(lds64);
     uint32_t* dump = reinterpret_cast<uint32_t*>(lds64) + kQueryBlock;     // [KC][64] after the 64 row words
-    const int32_t my_row = valid ? a.perm[p] : -1;
-    rows_lds[lane] = (valid && !active) ? my_row : -1;
+    rows_lds[lane] = (valid && !active) ? (asks ? my_row : -2 - my_row) : -1;   // -1: nothing to write; <= -2: all-padding row
 #ifndef FG_TILE_PROF
     if (COUNT && valid) a.out_cand[my_row] = cand;
 #endif
@@ -282,7 +288,7 @@ k_query_tile_sorted(QueryArgs a)
         if (pass) __syncthreads();
 #pragma unroll
         for (int i = 0; i < KC; ++i) {
-            const bool real = best[i] != ~0ull;
+            const bool real = best[i] < kEmptyKey;
             const uint32_t word = pass == 0 ? (real ? (uint32_t)best[i] : 0xffffffffu)      // index or -1
                                             : (real ? (uint32_t)(best[i] >> 32) : 0u);       // distance bits or 0.0f
             dump[i * kQueryBlock + lane] = word;
@@ -291,10 +297,11 @@ k_query_tile_sorted(QueryArgs a)
         for (int32_t r0 = 0; r0 < kQueryBlock; r0 += per_iter) {
             const int32_t ql = r0 + sub;
             if (sub >= per_iter || ql >= kQueryBlock) continue;
-            const int32_t row = rows_lds[ql];
-            if (row < 0) continue;
+            const int32_t enc = rows_lds[ql];
+            if (enc == -1) continue;
+            const int32_t row = enc >= 0 ? enc : -2 - enc;
             for (int32_t j = j0; j < k; j += kQueryBlock) {
-                uint32_t word = pass == 0 ? (uint32_t)row : 0u;             // slot 0: the row itself at distance 0
+                uint32_t word = pass == 0 ? (enc >= 0 ? (uint32_t)row : 0xffffffffu) : 0u;   // slot 0: the row itself at distance 0
                 if (j > 0) word = dump[(KC - cap + j - 1) * kQueryBlock + ql];
                 if (pass == 0) a.out_idx[(int64_t)row * k + j] = (int32_t)word;
                 else a.out_d2[(int64_t)row * k + j] = __uint_as_float(word);

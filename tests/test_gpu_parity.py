@@ -178,6 +178,41 @@ def test_tile_and_list_kernels_both_run_and_agree_with_the_plain_walk():
         assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "plain walk nb=%d" % nb)
 
 
+def gpu_knn_dir(x, rs, direction, k, n_bins=0, d_bin=0):
+    idx, d2 = B.fg_binned_select_knn_dir(torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV),
+                                         torch.from_numpy(direction).to(DEV), k, n_bins, d_bin)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), d2.cpu().numpy()
+
+
+@pytest.mark.parametrize("d,k", [(2, 8), (3, 16), (3, 40), (5, 70), (4, 100)])
+def test_direction_flags(d, k):
+    """Algorithm 2's useDir / dir[]: 0 = neighbour only, 1 = query only, 2 = neither, else both."""
+    sizes = [900, 0, 1500, 70, 3]
+    n = sum(sizes)
+    x, rs = W.uniform(n, d, seed=70 + d, sizes=sizes)
+    rng = np.random.Generator(np.random.PCG64(71 + k))
+    patterns = [rng.integers(0, 4, size=n), np.where(rng.random(n) < 0.9, 1, 0), np.ones(n), np.zeros(n),
+                np.full(n, 2), np.full(n, 3), rng.integers(-3, 9, size=n)]
+    for direction in patterns:
+        direction = direction.astype(np.int32)
+        oi, od = oracle.knn(x, rs, k, direction=direction)
+        for nb, db in [(0, 0), (6, min(d, 3)), (1, 2)]:
+            gi, gd = gpu_knn_dir(x, rs, direction, k, nb, db)
+            assert_exact(gi, gd, oi, od, "dir d=%d k=%d nb=%d" % (d, k, nb))
+    # plain walk kernel with flags
+    direction = patterns[0].astype(np.int32)
+    oi, od = oracle.knn(x, rs, k, direction=direction)
+    xt, rt = torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV)
+    bn = B.fg_bin_points(xt, rt, k)
+    dt = torch.from_numpy(direction).to(DEV)
+    bn.raw.dir = dt.data_ptr()
+    bn.raw.query_algo = 1
+    gi, gd = B.fg_query_binned(bn, rt, k)
+    torch.cuda.synchronize()
+    assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "dir plain walk")
+
+
 def test_candidate_counts():
     """n_bins = 1: every query scans its whole row split minus itself (brute force through the
     same kernel); finer grids scan fewer candidates, never fewer than k-1."""

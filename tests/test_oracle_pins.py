@@ -48,6 +48,35 @@ def exhaustive_knn(coords, row_splits, k):
     return idx, d2o
 
 
+def exhaustive_knn_dir(coords, row_splits, k, direction):
+    """Direction flags of Algorithm 2 applied to the exhaustive sort: rows of non-querying points are
+    all padding; non-neighbour points are removed from every candidate set."""
+    coords = np.asarray(coords, dtype=np.float32)
+    n = coords.shape[0]
+    idx = np.full((n, k), -1, dtype=np.int32)
+    d2o = np.zeros((n, k), dtype=np.float32)
+    is_query = ~np.isin(direction, (0, 2))
+    is_nb = ~np.isin(direction, (1, 2))
+    for s in range(len(row_splits) - 1):
+        b, e = int(row_splits[s]), int(row_splits[s + 1])
+        for v in range(b, e):
+            if not is_query[v]:
+                continue
+            others = np.array([u for u in range(b, e) if u != v and is_nb[u]], dtype=np.int64)
+            idx[v, 0] = v
+            if len(others) == 0:
+                continue
+            acc = None
+            for c in range(coords.shape[1]):
+                delta = (coords[v, c] - coords[others, c]).astype(np.float32)
+                sq = (delta * delta).astype(np.float32)
+                acc = sq if acc is None else (acc + sq).astype(np.float32)
+            order = np.lexsort((others, acc))[: k - 1]
+            idx[v, 1:1 + len(order)] = others[order]
+            d2o[v, 1:1 + len(order)] = acc[order]
+    return idx, d2o
+
+
 def assert_same(a_idx, a_d2, b_idx, b_d2):
     assert np.array_equal(a_idx, b_idx)
     assert np.array_equal(a_d2.view(np.uint32), b_d2.view(np.uint32))   # bit-exact, incl. signed zero
@@ -67,6 +96,33 @@ def test_matches_exhaustive_sort_ragged_with_ties(d):
     x, rs = W.quantised(n, d, levels=3, seed=7 + d, sizes=sizes)
     for k in (1, 2, 6, 40):
         assert_same(*oracle.knn(x, rs, k), *exhaustive_knn(x, rs, k))
+
+
+@pytest.mark.parametrize("d", [2, 3, 6])
+def test_direction_flags_match_exhaustive_sort(d):
+    sizes = [0, 9, 1, 40, 3]
+    n = sum(sizes)
+    x, rs = W.quantised(n, d, levels=4, seed=17 + d, sizes=sizes)
+    rng = np.random.Generator(np.random.PCG64(3 + d))
+    for direction in (rng.integers(0, 4, size=n), np.zeros(n), np.ones(n), np.full(n, 2), np.full(n, 3),
+                      rng.integers(0, 6, size=n)):
+        direction = direction.astype(np.int32)
+        for k in (1, 4, 45):
+            assert_same(*oracle.knn(x, rs, k, direction=direction), *exhaustive_knn_dir(x, rs, k, direction))
+    # flags that allow both roles everywhere change nothing
+    assert_same(*oracle.knn(x, rs, 5, direction=np.full(n, 3, dtype=np.int32)), *oracle.knn(x, rs, 5))
+
+
+def test_direction_flags_by_hand():
+    # points 0..3 on a line at 0, 1, 2, 4; flags: 0 = neighbour only, 1 = query only, 2 = neither, 3 = both
+    x = np.array([[0, 0], [1, 0], [2, 0], [4, 0]], dtype=np.float32)
+    rs = np.array([0, 4], dtype=np.int32)
+    idx, d2 = oracle.knn(x, rs, 3, direction=np.array([0, 1, 2, 3], dtype=np.int32))
+    assert idx.tolist() == [[-1, -1, -1],      # 0 asks nothing
+                            [1, 0, 3],         # 1 sees 0 (d2 1) and 3 (d2 9); 2 is nobody's neighbour
+                            [-1, -1, -1],      # 2 asks nothing
+                            [3, 0, -1]]        # 3 sees only 0 (1 and 2 are not neighbours)
+    assert d2.tolist() == [[0, 0, 0], [0, 1, 9], [0, 0, 0], [0, 16, 0]]
 
 
 def test_rows_variant_equals_full():
