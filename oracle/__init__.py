@@ -5,7 +5,7 @@ import this package.  It shares no code with the HIP path and never imports it.
 
 ``knn`` / ``knn_rows`` / ``knn_backward`` wrap the plain C in ``knn_oracle.c`` (brute-force
 definition of what Section 3 / Algorithm 2 of the paper computes, see that file's header).
-``paper_n_bins`` restates the bins-per-dimension heuristic of Section 3 (the displayed
+``oc_helper`` wraps ``oc_helper_oracle.c`` (Algorithm 3).  ``paper_n_bins`` restates the bins-per-dimension heuristic of Section 3 (the displayed
 equation and the clamp to [5, 30] stated under it).
 """
 from __future__ import annotations
@@ -19,6 +19,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "knn_oracle.c")
+_SRC_OC = os.path.join(_HERE, "oc_helper_oracle.c")
 _LIB = os.path.join(_HERE, "libknn_oracle.so")
 _lib = None
 
@@ -28,10 +29,11 @@ CFLAGS = ["-O3", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC", "-s
 
 def build(force: bool = False) -> str:
     """Compile knn_oracle.c with gcc (no FMA contraction, no fast-math)."""
-    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_OC))
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < newest
     if force or stale:
         tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm"])
+        subprocess.check_call(["gcc", *CFLAGS, "-o", tmp, _SRC, _SRC_OC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -56,6 +58,9 @@ def _load():
         lib.oracle_knn_backward.argtypes = [f32p, i32p, f32p, ctypes.c_int64, ctypes.c_int,
                                             ctypes.c_int, f64p, f64p]
         lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_oc_helper.restype = ctypes.c_int
+        lib.oracle_oc_helper.argtypes = [i32p, i32p, i32p, i32p, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                         ctypes.c_int64, ctypes.c_int64, ctypes.c_int, ctypes.c_int64, i32p, i32p]
         _lib = lib
     return _lib
 
@@ -135,6 +140,27 @@ def knn_backward(grad_d2, idx, coords):
     if rc != 0:
         raise ValueError("oracle_knn_backward: bad arguments")
     return g, a
+
+
+def oc_helper(asso_idx, unique_idx, unique_rs_asso, rs, n_maxuq: int, n_maxrs: int, calc_m_not: bool = True,
+              rot_block: int = 1):
+    """Index matrices of Algorithm 3 (Section 5).  Returns (M [n_maxuq, n_unique], M_not [n_maxrs, n_unique] or
+    None): entry `fill` of object k is M[fill, k], the storage order of the paper's index macro."""
+    asso_idx = np.ascontiguousarray(asso_idx, dtype=np.int32)
+    unique_idx = np.ascontiguousarray(unique_idx, dtype=np.int32)
+    unique_rs_asso = np.ascontiguousarray(unique_rs_asso, dtype=np.int32)
+    rs = np.ascontiguousarray(rs, dtype=np.int32)
+    n_unique = unique_idx.shape[0]
+    M = np.empty((n_maxuq, n_unique), dtype=np.int32)
+    M_not = np.empty((n_maxrs, n_unique), dtype=np.int32) if calc_m_not else None
+    rc = _load().oracle_oc_helper(_ptr(asso_idx, ctypes.c_int32), _ptr(unique_idx, ctypes.c_int32),
+                                  _ptr(unique_rs_asso, ctypes.c_int32), _ptr(rs, ctypes.c_int32),
+                                  asso_idx.shape[0], n_unique, rs.shape[0] - 1, n_maxuq, n_maxrs,
+                                  1 if calc_m_not else 0, rot_block, _ptr(M, ctypes.c_int32),
+                                  _ptr(M_not, ctypes.c_int32) if calc_m_not else None)
+    if rc != 0:
+        raise ValueError("oracle_oc_helper: bad arguments")
+    return M, M_not
 
 
 def paper_n_bins(n_points: int, n_segments: int, k: int, d: int, d_max: int = 5):

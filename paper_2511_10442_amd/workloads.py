@@ -173,6 +173,37 @@ def config5(n_per_segment: int = 1_000_000, n_segments: int = 5, k: int = 16,
                          % (n, n_hotspots, n_segments, k))
 
 
+def oc_association(sizes, objects_per_split: int, noise_frac: float, seed: int):
+    """Synthetic object-condensation association (input of Algorithm 3, Section 5): every row split gets
+    `objects_per_split` condensation points (vertices of the split); each other vertex is associated with one
+    of them (skewed sizes) or, with probability noise_frac, with nothing (-1).  Returns asso_idx [n],
+    unique_idx [n_unique], unique_rs_asso [n_unique], rs [S+1], n_maxuq, n_maxrs."""
+    rng = _rng(seed)
+    rs = _splits(sizes)
+    asso = np.full(int(rs[-1]), -1, dtype=np.int32)
+    uniq, uniq_rs = [], []
+    for s, size in enumerate(sizes):
+        if size == 0:
+            continue
+        b = int(rs[s])
+        n_obj = min(objects_per_split, size)
+        cps = np.sort(rng.choice(size, size=n_obj, replace=False)) + b
+        weights = rng.random(n_obj) ** 3 + 1e-3
+        pick = rng.choice(n_obj, size=size, p=weights / weights.sum())
+        a = cps[pick].astype(np.int32)
+        a[rng.random(size) < noise_frac] = -1
+        a[cps - b] = cps                              # a condensation point belongs to itself
+        asso[b:b + size] = a
+        uniq += cps.tolist()
+        uniq_rs += [s] * n_obj
+    unique_idx = np.asarray(uniq, dtype=np.int32)
+    unique_rs_asso = np.asarray(uniq_rs, dtype=np.int32)
+    counts = np.bincount(asso[asso >= 0], minlength=1)
+    n_maxuq = int(counts.max()) if counts.size else 1
+    n_maxrs = int(max(sizes)) if len(sizes) else 1
+    return asso, unique_idx, unique_rs_asso, rs, max(n_maxuq, 1), max(n_maxrs, 1)
+
+
 CONFIGS = {1: config1, 2: config2, 3: config3, 4: config4, 5: config5}
 
 
