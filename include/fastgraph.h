@@ -168,6 +168,32 @@ fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float*
                           const int32_t* row_splits, int64_t n, int32_t d, int32_t n_segments, int32_t k,
                           float* grad_coords, void* workspace, size_t workspace_bytes, void* stream);
 
+/* Object-condensation index matrices (Section 5, Algorithm 3).
+ *   asso_idx       [n_vert] int32  object id each vertex is associated with (any value that is no object id,
+ *                                  e.g. -1, means none)
+ *   unique_idx     [n_unique]      the object ids
+ *   unique_rs_asso [n_unique]      row split each object lives in (values outside 0..n_splits-1 are clamped)
+ *   rs             [n_splits+1]    row splits
+ *   M     [n_maxuq][n_unique] out  entry `fill` of object k at M[fill * n_unique + k] (the paper's index macro):
+ *                                  the vertices of the object's row split with asso_idx == unique_idx[k], in walk
+ *                                  order, at most n_maxuq of them, then -1
+ *   M_not [n_maxrs][n_unique] out  (only if calc_m_not != 0; may be NULL otherwise) the vertices of the walk that
+ *                                  are not associated with the object, then -1
+ * The walk of object k covers the first min(split size, n_maxrs) vertices of its row split, starting
+ * (k mod rot_block) vertices in and wrapping round (in the paper the offset is the thread index inside the launch
+ * block, whose size the paper does not state; rot_block = 1 gives plain ascending order).  A row of M stops at
+ * n_maxuq entries (the printed listing would write one more).  n_unique == 0: FG_OK, nothing enqueued.
+ * workspace: optional device scratch of fg_oc_helper_workspace_size() bytes, 256-byte aligned.  With it the
+ * walk is cut into chunks that run in parallel (much faster for long row splits); without it (NULL) one lane
+ * walks a whole row split, as in the paper.  Same result either way.
+ * Errors: FG_ERR_NULL, FG_ERR_BAD_SHAPE (negative sizes, n_maxuq < 1, n_maxrs < 1, rot_block < 1, n_splits < 1),
+ * FG_ERR_WORKSPACE (given but too small or misaligned). */
+fg_status fg_oc_helper_workspace_size(int64_t n_unique, int32_t n_maxrs, size_t* bytes /* host out */);
+fg_status fg_oc_helper(const int32_t* asso_idx, const int32_t* unique_idx, const int32_t* unique_rs_asso,
+                       const int32_t* rs, int64_t n_vert, int64_t n_unique, int32_t n_splits, int32_t n_maxuq,
+                       int32_t n_maxrs, int32_t calc_m_not, int32_t rot_block, int32_t* M, int32_t* M_not,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,7 +24,7 @@ FG_ERR_LAUNCH = 5
 
 EXPORTS = ["fg_status_string", "fg_auto_n_bins", "fg_workspace_size", "fg_bin_points",
            "fg_binned_select_knn", "fg_binned_select_knn_dir", "fg_binned_select_knn_counted", "fg_query_binned",
-           "fg_knn_backward"]
+           "fg_knn_backward", "fg_oc_helper", "fg_oc_helper_workspace_size"]
 
 
 class FgError(RuntimeError):
@@ -75,6 +75,10 @@ def lib() -> ctypes.CDLL:
         L.fg_query_binned.argtypes = [ctypes.POINTER(_Binning), vp, i64, i32, i32, i32, vp, vp, vp, vp]
         L.fg_knn_backward.restype = ctypes.c_int
         L.fg_knn_backward.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, vp, vp, sz, vp]
+        L.fg_oc_helper.restype = ctypes.c_int
+        L.fg_oc_helper.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.fg_oc_helper_workspace_size.restype = ctypes.c_int
+        L.fg_oc_helper_workspace_size.argtypes = [i64, i32, ctypes.POINTER(sz)]
         _lib = L
     return _lib
 
@@ -290,3 +294,33 @@ def fg_knn_backward(grad_d2: torch.Tensor, idx: torch.Tensor, coords: torch.Tens
                                  _ptr(grad_coords), _ptr(workspace),
                                  0 if workspace is None else workspace.numel(), _stream()), "fg_knn_backward")
     return grad_coords
+
+
+def fg_oc_helper_workspace_size(n_unique: int, n_maxrs: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().fg_oc_helper_workspace_size(n_unique, n_maxrs, ctypes.byref(out)), "fg_oc_helper_workspace_size")
+    return int(out.value)
+
+
+def fg_oc_helper(asso_idx: torch.Tensor, unique_idx: torch.Tensor, unique_rs_asso: torch.Tensor, rs: torch.Tensor,
+                 n_maxuq: int, n_maxrs: int, calc_m_not: bool = True, rot_block: int = 1, M=None, M_not=None,
+                 workspace="auto"):
+    """Index matrices of Algorithm 3: returns (M [n_maxuq, n_unique], M_not [n_maxrs, n_unique] or None).
+    workspace: "auto" allocates the scratch of the chunked kernels, None runs the single-kernel form."""
+    asso_idx = _dev(asso_idx, torch.int32, "asso_idx")
+    unique_idx = _dev(unique_idx, torch.int32, "unique_idx")
+    unique_rs_asso = _dev(unique_rs_asso, torch.int32, "unique_rs_asso")
+    rs = _dev(rs, torch.int32, "rs")
+    n_unique = unique_idx.numel()
+    if M is None:
+        M = torch.empty((n_maxuq, n_unique), dtype=torch.int32, device=asso_idx.device)
+    if calc_m_not and M_not is None:
+        M_not = torch.empty((n_maxrs, n_unique), dtype=torch.int32, device=asso_idx.device)
+    if isinstance(workspace, str):
+        workspace = torch.empty(max(256, fg_oc_helper_workspace_size(n_unique, n_maxrs)), dtype=torch.uint8,
+                                device=asso_idx.device)
+    _check(lib().fg_oc_helper(_ptr(asso_idx), _ptr(unique_idx), _ptr(unique_rs_asso), _ptr(rs), asso_idx.numel(),
+                              n_unique, rs.numel() - 1, n_maxuq, n_maxrs, 1 if calc_m_not else 0, rot_block,
+                              _ptr(M), _ptr(M_not) if calc_m_not else 0, _ptr(workspace),
+                              0 if workspace is None else workspace.numel(), _stream()), "fg_oc_helper")
+    return M, (M_not if calc_m_not else None)

@@ -32,7 +32,7 @@ QUERY_DIMS = range(2, 11)
 def units():
     """(source, object, extra flags)"""
     out = [(os.path.join(CSRC, f + ".hip"), os.path.join(OBJ, f + ".o"), [])
-           for f in ("fg_api", "fg_binning", "fg_backward")]
+           for f in ("fg_api", "fg_binning", "fg_backward", "fg_oc_helper")]
     for d in QUERY_DIMS:
         out.append((os.path.join(CSRC, "fg_query_inst.hip"), os.path.join(OBJ, "fg_query_d%d.o" % d),
                     ["-DFG_QUERY_D=%d" % d]))

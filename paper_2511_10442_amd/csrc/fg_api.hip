@@ -311,4 +311,30 @@ fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float*
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }
 
+fg_status fg_oc_helper_workspace_size(int64_t n_unique, int32_t n_maxrs, size_t* bytes)
+{
+    if (!bytes) return FG_ERR_NULL;
+    if (n_unique < 0 || n_unique >= ((int64_t)1 << 31) || n_maxrs < 1) return FG_ERR_BAD_SHAPE;
+    *bytes = align_up(oc_workspace_bytes(n_unique, n_maxrs));
+    return FG_OK;
+}
+
+fg_status fg_oc_helper(const int32_t* asso_idx, const int32_t* unique_idx, const int32_t* unique_rs_asso,
+                       const int32_t* rs, int64_t n_vert, int64_t n_unique, int32_t n_splits, int32_t n_maxuq,
+                       int32_t n_maxrs, int32_t calc_m_not, int32_t rot_block, int32_t* M, int32_t* M_not,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (n_vert < 0 || n_vert >= ((int64_t)1 << 31) || n_unique < 0 || n_unique >= ((int64_t)1 << 31) || n_splits < 1 ||
+        n_maxuq < 1 || n_maxrs < 1 || rot_block < 1)
+        return FG_ERR_BAD_SHAPE;
+    if (n_unique == 0) return FG_OK;
+    if (!asso_idx || !unique_idx || !unique_rs_asso || !rs || !M || (calc_m_not && !M_not)) return FG_ERR_NULL;
+    if (workspace && (((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < oc_workspace_bytes(n_unique, n_maxrs)))
+        return FG_ERR_WORKSPACE;
+    hipError_t e = launch_oc_helper(asso_idx, unique_idx, unique_rs_asso, rs, (int32_t)n_vert, (int32_t)n_unique, n_splits,
+                                    n_maxuq, n_maxrs, calc_m_not ? 1 : 0, rot_block, M, M_not, (int32_t*)workspace,
+                                    (hipStream_t)stream);
+    return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
+}
+
 }  // extern "C"

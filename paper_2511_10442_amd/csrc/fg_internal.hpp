@@ -45,6 +45,12 @@ hipError_t launch_query(const QueryArgs& a, int32_t d, int32_t d_bin, hipStream_
 hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, const int32_t* perm,
                            int32_t n, int32_t d, int32_t k, float* grad_coords, hipStream_t stream);
 
+hipError_t launch_oc_helper(const int32_t* asso_idx, const int32_t* unique_idx, const int32_t* unique_rs_asso,
+                            const int32_t* rs, int32_t n_vert, int32_t n_unique, int32_t n_splits, int32_t n_maxuq,
+                            int32_t n_maxrs, int32_t calc_m_not, int32_t rot_block, int32_t* M, int32_t* M_not,
+                            int32_t* counts /* workspace of oc_workspace_bytes(), or nullptr */, hipStream_t stream);
+size_t oc_workspace_bytes(int64_t n_unique, int32_t n_maxrs);
+
 // Direction flags (paper Algorithm 2, useDir / dir[]): 0 or 2 = issues no query, 1 or 2 = is nobody's
 // neighbour, anything else = both roles.
 __device__ __forceinline__ bool dir_is_query(int32_t f) { return f != 0 && f != 2; }

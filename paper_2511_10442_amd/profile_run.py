@@ -7,6 +7,8 @@
     --stage forward   fg_binned_select_knn `reps` times
     --stage backward  forward once, then fg_knn_backward `reps` times
     --stage all       forward + backward `reps` times
+    --stage oc        fg_oc_helper (Algorithm 3) `reps` times on 10 row splits of 100,000 vertices with 200
+                      object candidates each; prints its mean time and output bandwidth
     --calib-mb M      additionally run one plain elementwise copy kernel (torch.add(a, 0, out=b))
                       over M MiB in and M MiB out, `reps` times: the known-size reference for
                       scaling memory counters
@@ -23,7 +25,7 @@ sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--config", type=int, default=3)
-    ap.add_argument("--stage", default="query", choices=["query", "forward", "backward", "all", "none"])
+    ap.add_argument("--stage", default="query", choices=["query", "forward", "backward", "all", "oc", "none"])
     ap.add_argument("--reps", type=int, default=5)
     ap.add_argument("--n-bins", type=int, default=0)
     ap.add_argument("--d-bin", type=int, default=0)
@@ -42,6 +44,27 @@ def main() -> int:
             torch.add(a, 0.0, out=b)
         torch.cuda.synchronize()
     if args.stage == "none":
+        return 0
+    if args.stage == "oc":
+        import numpy as np
+        asso, uq, uqrs, rs_np, n_maxuq, n_maxrs = W.oc_association([100_000] * 10, 200, 0.1, seed=33)
+        t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+        A, U, R, S = t(asso), t(uq), t(uqrs), t(rs_np)
+        M = torch.empty((n_maxuq, len(uq)), dtype=torch.int32, device=dev)
+        Mn = torch.empty((n_maxrs, len(uq)), dtype=torch.int32, device=dev)
+        wsp = torch.empty(B.fg_oc_helper_workspace_size(len(uq), n_maxrs), dtype=torch.uint8, device=dev)
+        B.fg_oc_helper(A, U, R, S, n_maxuq, n_maxrs, True, 256, M, Mn, wsp)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.reps):
+            B.fg_oc_helper(A, U, R, S, n_maxuq, n_maxrs, True, 256, M, Mn, wsp)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.reps
+        out_bytes = (M.numel() + Mn.numel()) * 4
+        print("fg_oc_helper: %.3f ms, n_unique=%d n_maxuq=%d n_maxrs=%d, %.0f MB written -> %.0f GB/s"
+              % (ms, len(uq), n_maxuq, n_maxrs, out_bytes / 1e6, out_bytes / ms / 1e6))
         return 0
     w = W.CONFIGS[args.config]()
     x = torch.from_numpy(w.coords).to(dev)

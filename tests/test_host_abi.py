@@ -95,6 +95,13 @@ def test_argument_validation_without_gpu():
     assert L.fg_knn_backward(8, 8, 8, 8, 10, 3, 1, 4, 8, 256, 16, None) == B.FG_ERR_WORKSPACE
     assert L.fg_knn_backward(None, None, None, None, 0, 3, 1, 4, None, None, 0, None) == B.FG_OK
     assert L.fg_query_binned(None, 8, 10, 3, 1, 4, 8, 8, None, None) == B.FG_ERR_NULL
+    assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 4, 10, 1, 1, None, 8, None, 0, None) == B.FG_ERR_NULL
+    assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 4, 10, 1, 1, 8, None, None, 0, None) == B.FG_ERR_NULL
+    assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 0, 10, 0, 1, 8, None, None, 0, None) == B.FG_ERR_BAD_SHAPE
+    assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 4, 10, 0, 0, 8, None, None, 0, None) == B.FG_ERR_BAD_SHAPE
+    assert L.fg_oc_helper(None, None, None, None, 10, 0, 1, 4, 10, 1, 1, None, None, None, 0, None) == B.FG_OK
+    assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 4, 10, 0, 1, 8, None, 256, 8, None) == B.FG_ERR_WORKSPACE
+    assert B.fg_oc_helper_workspace_size(2000, 100000) >= (100000 // 128 + 1) * 2000 * 4
 
 
 def test_workspace_size_scales_linearly():
