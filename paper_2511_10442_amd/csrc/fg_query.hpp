@@ -1,4 +1,7 @@
-// General shell-expanding exact query kernel: one lane per query, any shell radius.
+// Per-lane geometry shared by all query kernels, and the general shell-expanding walk with one
+// lane per query (any shell radius).  The walk is the cross-check path (query_algo = 1) and the
+// list pass for K-1 > 64; the fast path is the tile kernel plus the one-query-per-wavefront list
+// kernel.
 //
 // What it computes (paper Section 3, Algorithm 2): for every point, the K-1 nearest other
 // points of its row split, found by scanning the bins on the surface of the hypercube of
@@ -173,30 +176,6 @@ struct ShellSearch : LaneGeom<D, DB> {
         }
     }
 
-    // staged points: LDS holds sorted positions [base, base+cnt); scan the part of [lo, hi) inside it
-    __device__ __forceinline__ void scan_staged(const float* stage, const int32_t* stage_idx, int32_t base,
-                                                int32_t cnt, int32_t lo, int32_t hi)
-    {
-        lo = lo > base ? lo : base;
-        hi = hi < base + cnt ? hi : base + cnt;
-        for (int32_t q = lo; q < hi; ++q) {
-            if (q == self_pos) continue;
-            const int32_t i = q - base;
-            float diff = x[0] - stage[i];
-            float d2 = diff * diff;
-#pragma unroll
-            for (int c = 1; c < D; ++c) {
-                diff = x[c] - stage[c * kStageChunk + i];
-                d2 = d2 + diff * diff;
-            }
-            if (COUNT) ++cand;
-            uint32_t bits = __float_as_uint(d2);
-            if (bits > (uint32_t)(tau >> 32)) continue;
-            if (dir && !dir_is_neighbour(dir[stage_idx[i]])) continue;
-            offer(((uint64_t)bits << 32) | (uint32_t)stage_idx[i]);
-        }
-    }
-
     template <int LVL>
     __device__ __forceinline__ void visit(int32_t r, int32_t flat, float partial, bool surf)
     {
@@ -292,18 +271,6 @@ __device__ __forceinline__ void write_row(ShellSearch<D, DB, COUNT>& s, const Qu
 #endif
 }
 
-// ---- main pass: one wavefront per tile of 64 consecutive bin-ordered queries ----------------
-//
-// The shell walk of Algorithm 2 is made wave-uniform: all 64 lanes step through the same
-// column offsets (offsets in the first DB-1 binning dimensions) of the same shell at the same
-// time.  Because the queries of a tile are consecutive in bin order, the bins they need for one
-// column offset form one contiguous range of sorted points; that range is staged through LDS
-// in chunks with coalesced loads and every lane scans only its own sub-range of the chunk.
-// Lanes certify independently after every shell.  When few lanes are left the wave stops and
-// hands them to the list kernel below, so that a handful of far-searching queries (isolated
-// points) does not keep 64 lanes busy.
-
-
 // Wave-wide min / max of one int per lane with DPP row shifts and row broadcasts (6 VALU
 // operations and one readlane each); the result is uniform.
 __device__ __forceinline__ int32_t wave_min_i32(int32_t v)
@@ -339,111 +306,7 @@ __device__ __forceinline__ int32_t wave_max_i32(int32_t v)
     return __builtin_amdgcn_readlane(v, 63);
 }
 
-template <int D, int DB, bool COUNT>
-__global__ void __launch_bounds__(kQueryBlock)
-k_query_tile(QueryArgs a)
-{
-    extern __shared__ uint64_t lds64[];
-    const int lane = threadIdx.x;
-    const int32_t cap = a.k - 1;
-    float* stage = reinterpret_cast<float*>(lds64 + (size_t)(cap > 0 ? cap : 0) * kQueryBlock);
-    int32_t* stage_idx = reinterpret_cast<int32_t*>(stage + D * kStageChunk);
-
-    const int32_t p = blockIdx.x * kQueryBlock + lane;
-    const bool valid = p < a.n;
-    ShellSearch<D, DB, COUNT> s;
-    init_lane(s, a, valid ? p : a.n - 1, lds64 + lane);   // dead lanes shadow the last point, never scan or write
-    s.self_pos = p;
-    bool active = valid && cap > 0 && !(a.dir && !dir_is_query(a.dir[a.perm[valid ? p : a.n - 1]]));
-
-    for (int32_t R = 0;; ++R) {   // ends at the latest at R = n_bins - 1, when every lane's cube covers its grid
-        const int32_t side = 2 * R + 1;
-        int32_t ncols = 1;
-#pragma unroll
-        for (int c = 0; c < DB - 1; ++c) ncols *= side;
-        for (int32_t t = 0; t < ncols; ++t) {
-            // column offsets, wave-uniform; digit v of t maps to 0, +1, -1, +2, -2, ... (centre first)
-            int32_t o[DB - 1];
-            bool surf = false;
-            {
-                int32_t rem = t;
-#pragma unroll
-                for (int c = DB - 2; c >= 0; --c) {
-                    int32_t v = rem % side;
-                    rem /= side;
-                    o[c] = (v & 1) ? ((v + 1) >> 1) : -(v >> 1);
-                    surf = surf || o[c] == R || o[c] == -R;
-                }
-            }
-            bool ok = active;
-            float partial = 0.0f;
-            int32_t flat = 0;
-#pragma unroll
-            for (int c = 0; c < DB - 1; ++c) {
-                const int32_t j = s.cc[c] + o[c];
-                ok = ok && j >= 0 && j < s.neff[c];
-                const float g = s.gap(c, j, o[c]);
-                partial += g * g;
-                flat = flat * a.n_bins + j;
-            }
-            ok = ok && !s.cannot_improve(partial);
-            int32_t a1 = 0, b1 = 0, a2 = 0, b2 = 0;
-            if (ok) {
-                const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
-                const int32_t row = s.seg_cell0 + flat * a.n_bins;
-                if (surf) {
-                    const int32_t za = cz - R < 0 ? 0 : cz - R;
-                    const int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
-                    a1 = a.bounds[row + za];
-                    b1 = a.bounds[row + zb + 1];
-                } else {
-                    if (cz - R >= 0) {
-                        const float g = s.gap(DB - 1, cz - R, -R);
-                        if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[row + cz - R]; b1 = a.bounds[row + cz - R + 1]; }
-                    }
-                    if (cz + R <= nz - 1) {
-                        const float g = s.gap(DB - 1, cz + R, R);
-                        if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[row + cz + R]; b2 = a.bounds[row + cz + R + 1]; }
-                    }
-                }
-            }
-            int32_t lo = 0x7fffffff, hi = 0;
-            if (b1 > a1) { lo = a1; hi = b1; }
-            if (b2 > a2) { lo = a2 < lo ? a2 : lo; hi = b2 > hi ? b2 : hi; }
-            const int32_t PA = wave_min_i32(lo), PB = wave_max_i32(hi);
-            for (int32_t base = PA; base < PB; base += kStageChunk) {
-                const int32_t cnt = PB - base < kStageChunk ? PB - base : kStageChunk;
-                __syncthreads();
-                for (int32_t i = lane; i < cnt; i += kQueryBlock) {
-#pragma unroll
-                    for (int c = 0; c < D; ++c) stage[c * kStageChunk + i] = a.soa[(int64_t)c * a.soa_stride + base + i];
-                    stage_idx[i] = a.perm[base + i];
-                }
-                __syncthreads();
-                s.scan_staged(stage, stage_idx, base, cnt, a1, b1);
-                s.scan_staged(stage, stage_idx, base, cnt, a2, b2);
-            }
-        }
-        if (active && s.certified(R)) active = false;
-        const int32_t n_active = __popcll(__ballot(active));
-        if (n_active == 0) break;
-        if (R >= 1 && n_active <= a.defer_lanes) break;
-    }
-
-    // unfinished lanes go to the work list (wave-aggregated append); the rest write their rows
-    const uint64_t mask = __ballot(active);
-    if (mask) {
-        int32_t base = 0;
-        const int leader = __ffsll((unsigned long long)mask) - 1;
-        if (lane == leader) base = atomicAdd(a.work_count, __popcll(mask));
-        base = __shfl(base, leader, 64);
-        if (active) a.work_list[base + __popcll(mask & ((1ull << lane) - 1))] = p;
-    }
-    if (valid && !active) write_row(s, a, p, false);
-    else if (COUNT && valid) a.out_cand[a.perm[p]] = s.cand;   // work done here counts too
-}
-
-// ---- list pass: the general one-lane-per-query shell walk over the deferred queries ---------
+// ---- list pass, one lane per query: the general shell walk over the deferred queries (used when K-1 > 64) ----
 template <int D, int DB, bool COUNT>
 __global__ void __launch_bounds__(kQueryBlock)
 k_query_list(QueryArgs a)

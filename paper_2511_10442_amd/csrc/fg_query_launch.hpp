@@ -39,10 +39,12 @@ static hipError_t launch_query_impl(const QueryArgs& a, hipStream_t stream)
     } else if (cap <= 64) {
         const size_t lds = tile_sorted_lds_bytes<64, D>();
         hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 64, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
-    } else {   // larger K: best list as a heap in LDS
-        const size_t tile_bytes = heap_bytes + (size_t)(D + 1) * kStageChunk * sizeof(float);
-        allow_lds(k_query_tile<D, DB, COUNT>, tile_bytes);
-        hipLaunchKernelGGL((k_query_tile<D, DB, COUNT>), dim3(grid), dim3(kQueryBlock), tile_bytes, stream, a);
+    } else if (cap <= 96) {
+        const size_t lds = tile_sorted_lds_bytes<96, D>();
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 96, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
+    } else {
+        const size_t lds = tile_sorted_lds_bytes<128, D>();
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 128, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     }
     if (cap <= 64) {   // one query per wavefront
         const int list_grid = a.n < 8192 ? a.n : 8192;

@@ -14,7 +14,7 @@
 //     at the end of every shell, all lanes absorb their pending keys into the sorted register
 //     list with a fixed merging network (no data-dependent addressing, no LDS round trips);
 //   * keys are 64-bit (distance bits << 32 | original index); slots beyond K-1 are pinned with
-//     zero keys so that the last register is always the (K-1)-th best (list sizes 16/32/48/64);
+//     zero keys so that the last register is always the (K-1)-th best (list sizes 16/32/48/64/96/128);
 //   * finished rows leave through LDS so that each output row is written as contiguous bytes;
 //   * lanes still uncertified when few are left are handed to the list kernel.
 #pragma once
@@ -27,7 +27,7 @@ namespace fg {
 #define FG_TILE_WAVES32 3
 #endif
 // waves per SIMD the register allocator aims at: the sorted list alone takes 2*KC registers
-template <int KC> constexpr int tile_waves() { return KC <= 16 ? 4 : (KC == 32 ? FG_TILE_WAVES32 : 2); }
+template <int KC> constexpr int tile_waves() { return KC <= 16 ? 4 : (KC == 32 ? FG_TILE_WAVES32 : (KC <= 64 ? 2 : 1)); }
 constexpr int kPend = 16;   // pending keys per lane between two merges
 struct Ranges { int32_t a1, b1, a2, b2; };
 
