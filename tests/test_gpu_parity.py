@@ -321,3 +321,44 @@ def test_backward_overwrites_and_ignores_padding():
                             torch.full((100, 3), 7.0, dtype=torch.float32, device=DEV))
     torch.cuda.synchronize()
     assert np.all(out.cpu().numpy() == 0.0)
+
+
+def test_forward_and_backward_replay_in_a_hip_graph():
+    """The library enqueues only kernels (counters are cleared by fill kernels, not memset nodes) and never
+    synchronises or allocates, so a whole step can be captured once and replayed.  Every replay is checked
+    against the oracle, with eager work and synchronisations in between."""
+    x, rs = W.uniform(20000, 3, seed=91, sizes=[12000, 8000])
+    k = 16
+    g = W.upstream_grad(20000, k, seed=92)
+    oi, od = oracle.knn(x, rs, k)
+    ref, asum = oracle.knn_backward(g, oi, x)
+    xt, rt, gt = torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV), torch.from_numpy(g).to(DEV)
+    ws = B.alloc_workspace(20000, 3, 2, k, 0, 0, DEV)
+    out_i = torch.empty((20000, k), dtype=torch.int32, device=DEV)
+    out_d = torch.empty((20000, k), dtype=torch.float32, device=DEV)
+    grad = torch.empty((20000, 3), dtype=torch.float32, device=DEV)
+
+    def step():
+        B.fg_binned_select_knn(xt, rt, k, 0, 0, ws, out_i, out_d)
+        B.fg_knn_backward(gt, out_i, xt, rt, grad, ws)
+
+    step()                                   # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out_i.fill_(-7)
+        out_d.fill_(-1.0)
+        grad.fill_(5.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_exact(out_i.cpu().numpy(), out_d.cpu().numpy(), oi, od, "graph replay %d" % rep)
+        grad_close(grad.cpu().numpy(), ref, asum)
+        junk = (xt * 2.0).sum().item()       # eager work between the replays
+        assert junk == junk
