@@ -41,15 +41,14 @@ constexpr size_t kAlign = 256;
 // so bins per dimension = margin * (n_elems * V_d / K)^(1/d).  Same functional form as
 // the paper's heuristic (a power 1/d of n_elems / K), with the constant 32 replaced by V_d and
 // the exponent taken over all d coordinates because the distance is.  Binning dimensions: all of
-// them up to 3; the first 3 for d = 4; the first 5 from d = 5 on (measured on uniform data).
+// them up to 5, the first 5 beyond (the paper's limit).
 // From d = 6 on a cube of 3 bins per side wastes most of its volume outside the ball, and
 // smaller bins searched two shells deep (with box pruning) measured faster.
 // Margins measured on uniform data (1e5..1e6 points, K = 10..100) and on the clustered
-// configurations.  For d <= 3 and d = 5 the bin width is ~1.1 r_K: finer grids are as fast or
-// faster on clustered data and for K >= 40, but for small K a large share of the queries then
-// needs a second shell and leaves the tile kernel.  d = 4 (3 of 4 dimensions binned) ~0.8 r_K,
-// d >= 6 ~0.6 r_K.
-constexpr double kTunedMarginByDim[11] = {0, 0, 0.9, 0.9, 1.2, 0.9, 1.6, 1.6, 1.6, 1.6, 1.6};
+// configurations.  For d <= 5 the bin width is ~1.1 r_K: finer grids are as fast or faster on
+// clustered data and for K >= 40, but for small K a large share of the queries then needs a
+// second shell and leaves the tile kernel.  d >= 6: ~0.6 r_K.
+constexpr double kTunedMarginByDim[11] = {0, 0, 0.9, 0.9, 0.9, 0.9, 1.6, 1.6, 1.6, 1.6, 1.6};
 constexpr int32_t kTunedMaxBins = 1024;
 constexpr int32_t kDefaultDeferLanes = 24;
 constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
@@ -158,7 +157,7 @@ fg_status fg_auto_n_bins(int64_t n, int32_t n_segments, int32_t k, int32_t d, in
         return FG_OK;
     }
     // mode 1: bin width ~ radius of the K-ball at mean density (kTunedMarginByDim, kTunedMaxBins)
-    const int32_t db = d <= 3 ? d : (d == 4 ? 3 : 5);
+    const int32_t db = d < 5 ? d : 5;
     const double unit_ball = pow(M_PI, 0.5 * d) / tgamma(0.5 * d + 1.0);
     const double margin = kTunedMarginByDim[d];
     double x = n_elems > 0 ? margin * pow(n_elems * unit_ball / (double)k, 1.0 / d) : 1.0;
