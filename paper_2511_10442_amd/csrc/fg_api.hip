@@ -50,7 +50,7 @@ constexpr size_t kAlign = 256;
 // second shell and leaves the tile kernel.  d >= 6: ~0.6 r_K.
 constexpr double kTunedMarginByDim[11] = {0, 0, 0.9, 0.9, 0.9, 0.9, 1.6, 1.6, 1.6, 1.6, 1.6};
 constexpr int32_t kTunedMaxBins = 1024;
-constexpr int32_t kDefaultDeferLanes = 24;
+constexpr int32_t kDefaultDeferLanes = 6;
 constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -122,6 +122,8 @@ fg_status resolve_bins(int64_t n, int32_t d, int32_t n_segments, int32_t k, int3
 
 using namespace fg;
 
+static int32_t backward_morton_bits(int64_t n, int32_t d, int32_t n_segments, int32_t k, int32_t* d_bin);
+
 extern "C" {
 
 const char* fg_status_string(fg_status status)
@@ -177,19 +179,34 @@ fg_status fg_workspace_size(int64_t n, int32_t d, int32_t n_segments, int32_t k,
     if (st != FG_OK) return st;
     st = resolve_bins(n, d, n_segments, k, &n_bins, &d_bin);
     if (st != FG_OK) return st;
-    *bytes = make_layout(n, d, n_segments, n_bins, d_bin).total;
+    size_t need = make_layout(n, d, n_segments, n_bins, d_bin).total;
+    int32_t db_b = 0;
+    const int32_t bits = backward_morton_bits(n, d, n_segments, k, &db_b);   // fg_knn_backward's own grid
+    if (bits > 0) {
+        const size_t need_b = make_layout(n, d, n_segments, 1 << bits, db_b).total;
+        if (need_b > need) need = need_b;
+    }
+    *bytes = need;
     return FG_OK;
 }
 
-fg_status fg_bin_points(const float* coords, const int32_t* row_splits, int64_t n, int32_t d,
-                        int32_t n_segments, int32_t k_hint, int32_t n_bins, int32_t d_bin,
-                        void* workspace, size_t workspace_bytes, fg_binning* view, void* stream)
+// Bits per dimension of the bit-interleaved bin order the backward pass sorts its rows by: the power of two
+// nearest to the automatic bin count (the order only has to be spatially coherent, any grid will do).
+static int32_t backward_morton_bits(int64_t n, int32_t d, int32_t n_segments, int32_t k, int32_t* d_bin)
 {
-    if (!view) return FG_ERR_NULL;
-    fg_status st = check_problem(n, d, n_segments, k_hint);
-    if (st != FG_OK) return st;
-    st = resolve_bins(n, d, n_segments, k_hint, &n_bins, &d_bin);
-    if (st != FG_OK) return st;
+    int32_t nb = 0;
+    if (fg_auto_n_bins(n, n_segments, k, d, 1, &nb, d_bin) != FG_OK) return 0;
+    int32_t bits = (int32_t)floor(log2((double)(nb < 2 ? 2 : nb)) + 0.5);
+    if (bits < 1) bits = 1;
+    while (bits > 1 && (bits * *d_bin > 24 || pow(2.0, bits * *d_bin) * n_segments > (double)FG_MAX_TOTAL_BINS)) --bits;
+    return bits;
+}
+
+// n_bins, d_bin resolved and validated by the caller
+static fg_status bin_points_impl(const float* coords, const int32_t* row_splits, int64_t n, int32_t d,
+                                 int32_t n_segments, int32_t n_bins, int32_t d_bin, int32_t morton_bits,
+                                 void* workspace, size_t workspace_bytes, fg_binning* view, void* stream)
+{
     if (!coords && n > 0) return FG_ERR_NULL;
     if (!row_splits || !workspace) return FG_ERR_NULL;
     const Layout L = make_layout(n, d, n_segments, n_bins, d_bin);
@@ -213,9 +230,22 @@ fg_status fg_bin_points(const float* coords, const int32_t* row_splits, int64_t 
     hipError_t e = launch_binning(coords, row_splits, (int32_t)n, d, n_segments, n_bins, d_bin, L.total_bins,
                                   (uint32_t*)(ws + L.keys), (float*)(ws + L.geom), (int32_t*)(ws + L.bin_idx),
                                   (int32_t*)(ws + L.rank), (int32_t*)(ws + L.perm), (float*)(ws + L.soa),
-                                  L.soa_stride, (int32_t*)(ws + L.bounds), (int32_t*)(ws + L.partials),
+                                  L.soa_stride, (int32_t*)(ws + L.bounds), (int32_t*)(ws + L.partials), morton_bits,
                                   (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
+}
+
+fg_status fg_bin_points(const float* coords, const int32_t* row_splits, int64_t n, int32_t d,
+                        int32_t n_segments, int32_t k_hint, int32_t n_bins, int32_t d_bin,
+                        void* workspace, size_t workspace_bytes, fg_binning* view, void* stream)
+{
+    if (!view) return FG_ERR_NULL;
+    fg_status st = check_problem(n, d, n_segments, k_hint);
+    if (st != FG_OK) return st;
+    st = resolve_bins(n, d, n_segments, k_hint, &n_bins, &d_bin);
+    if (st != FG_OK) return st;
+    return bin_points_impl(coords, row_splits, n, d, n_segments, n_bins, d_bin, 0, workspace, workspace_bytes, view,
+                           stream);
 }
 
 fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int64_t n, int32_t d,
@@ -301,8 +331,14 @@ fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float*
     if (row_splits && workspace && n_segments >= 1) {
         // bin the points once more to get a spatially coherent row order (the forward's workspace
         // is scratch by contract, so nothing of it is assumed to survive)
+        // rows sorted by bit-interleaved bin: 256 consecutive rows then form a compact block in space and
+        // share more destinations than a run of bins along the last dimension would
         fg_binning view;
-        st = fg_bin_points(coords, row_splits, n, d, n_segments, k, 0, 0, workspace, workspace_bytes, &view, stream);
+        int32_t db = 0;
+        const int32_t bits = backward_morton_bits(n, d, n_segments, k, &db);
+        if (bits < 1) return FG_ERR_BAD_SHAPE;
+        st = bin_points_impl(coords, row_splits, n, d, n_segments, 1 << bits, db, bits, workspace, workspace_bytes, &view,
+                             stream);
         if (st != FG_OK) return st;
         perm = view.perm;
     }

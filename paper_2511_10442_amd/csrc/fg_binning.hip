@@ -168,8 +168,9 @@ constexpr int kAssignProbes = 8;
 template <int DB>
 __global__ void __launch_bounds__(kBlock)
 k_assign(const float* __restrict__ coords, const int32_t* __restrict__ row_splits, int32_t n, int32_t d,
-         int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, const float* __restrict__ geom,
-         int32_t* __restrict__ bin_idx, int32_t* __restrict__ rank, int32_t* __restrict__ counters)
+         int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, int32_t morton_bits,
+         const float* __restrict__ geom, int32_t* __restrict__ bin_idx, int32_t* __restrict__ rank,
+         int32_t* __restrict__ counters)
 {
     __shared__ int32_t keys[kAssignSlots];
     __shared__ int32_t cnts[kAssignSlots];     // block-local population, then the block's base in the bin
@@ -185,9 +186,19 @@ k_assign(const float* __restrict__ coords, const int32_t* __restrict__ row_split
         const float* p = coords + i * d;
         const float* g = geom + (int64_t)s * DB * kGeomStride;
         int32_t f = 0;
+        if (morton_bits == 0) {                 // row-major, last dimension fastest (what the query kernels expect)
 #pragma unroll
-        for (int c = 0; c < DB; ++c)
-            f = f * n_bins + cell_of(p[c], g[c * kGeomStride + 0], g[c * kGeomStride + 1], n_bins);
+            for (int c = 0; c < DB; ++c)
+                f = f * n_bins + cell_of(p[c], g[c * kGeomStride + 0], g[c * kGeomStride + 1], n_bins);
+        } else {                                // bit-interleaved: consecutive bins form compact blocks in space
+            int32_t cell[DB];
+#pragma unroll
+            for (int c = 0; c < DB; ++c) cell[c] = cell_of(p[c], g[c * kGeomStride + 0], g[c * kGeomStride + 1], n_bins);
+            for (int b = 0; b < morton_bits; ++b) {
+#pragma unroll
+                for (int c = 0; c < DB; ++c) f |= ((cell[c] >> b) & 1) << (b * DB + (DB - 1 - c));
+            }
+        }
         f += s * cells_per_segment;
         flat[it] = f;
         bin_idx[i] = f;
@@ -314,7 +325,8 @@ k_scatter(const float* __restrict__ coords, int32_t n, const int32_t* __restrict
 
 template <int DB>
 static void launch_bbox_assign(bool assign, const float* coords, const int32_t* row_splits, int32_t n, int32_t d,
-                               int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, uint32_t* bbox_keys,
+                               int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, int32_t morton_bits,
+                               uint32_t* bbox_keys,
                                const float* geom, int32_t* bin_idx, int32_t* rank, int32_t* counters,
                                hipStream_t stream)
 {
@@ -323,7 +335,8 @@ static void launch_bbox_assign(bool assign, const float* coords, const int32_t* 
                            row_splits, n, d, n_segments, bbox_keys);
     else
         hipLaunchKernelGGL(k_assign<DB>, dim3((n + kAssignChunk - 1) / kAssignChunk), dim3(kBlock), 0, stream, coords,
-                           row_splits, n, d, n_segments, n_bins, cells_per_segment, geom, bin_idx, rank, counters);
+                           row_splits, n, d, n_segments, n_bins, cells_per_segment, morton_bits, geom, bin_idx, rank,
+                           counters);
 }
 
 template <int D>
@@ -339,7 +352,7 @@ hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_
                           int32_t n_segments, int32_t n_bins, int32_t d_bin, int64_t total_bins,
                           uint32_t* bbox_keys, float* geom, int32_t* bin_idx, int32_t* rank,
                           int32_t* perm, float* soa, int64_t soa_stride, int32_t* bounds,
-                          int32_t* scan_partials, hipStream_t stream)
+                          int32_t* scan_partials, int32_t morton_bits, hipStream_t stream)
 {
     const int64_t n_counters = total_bins + 1;
     const int32_t n_keys = n_segments * d_bin;
@@ -354,13 +367,13 @@ hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_
 #define FG_DB_SWITCH(ASSIGN)                                                                                       \
     switch (d_bin) {                                                                                               \
         case 2: launch_bbox_assign<2>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
-                                      bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
+                                      morton_bits, bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
         case 3: launch_bbox_assign<3>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
-                                      bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
+                                      morton_bits, bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
         case 4: launch_bbox_assign<4>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
-                                      bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
+                                      morton_bits, bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
         case 5: launch_bbox_assign<5>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
-                                      bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
+                                      morton_bits, bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
         default: return hipErrorInvalidValue;                                                                      \
     }
     FG_DB_SWITCH(false)

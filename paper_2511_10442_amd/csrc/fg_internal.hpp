@@ -36,7 +36,9 @@ hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_
                           int32_t n_segments, int32_t n_bins, int32_t d_bin, int64_t total_bins,
                           uint32_t* bbox_keys, float* geom, int32_t* bin_idx, int32_t* rank,
                           int32_t* perm, float* soa, int64_t soa_stride, int32_t* bounds,
-                          int32_t* scan_partials, hipStream_t stream);
+                          int32_t* scan_partials,
+                          int32_t morton_bits /* 0: row-major bins; b > 0: n_bins = 2^b, bit-interleaved bin order */,
+                          hipStream_t stream);
 
 // d = 2..10, d_bin = 2..min(d,5)
 hipError_t launch_query(const QueryArgs& a, int32_t d, int32_t d_bin, hipStream_t stream);

@@ -105,10 +105,12 @@ def test_argument_validation_without_gpu():
 
 
 def test_workspace_size_scales_linearly():
-    a = B.fg_workspace_size(100_000, 3, 1, 16, 20, 3)
-    b = B.fg_workspace_size(200_000, 3, 1, 16, 20, 3)
+    # (the size also covers the grid fg_knn_backward bins its rows with: a power of two near the automatic
+    #  bin count, so compare sizes whose explicit grid is the larger of the two)
+    a = B.fg_workspace_size(100_000, 3, 1, 16, 40, 3)
+    b = B.fg_workspace_size(200_000, 3, 1, 16, 40, 3)
     # per point: bin_idx + rank + perm + work list + d coordinates = (4 + d) words
     assert abs((b - a) - 100_000 * 4 * 7) < 4096
-    c = B.fg_workspace_size(100_000, 3, 1, 16, 40, 3)
-    assert abs((c - a) - (40 ** 3 - 20 ** 3) * 4) < 8192
+    c = B.fg_workspace_size(100_000, 3, 1, 16, 60, 3)
+    assert abs((c - a) - (60 ** 3 - 40 ** 3) * 4) < 8192
     assert B.fg_workspace_size(0, 3, 1, 16) >= 0
