@@ -14,6 +14,9 @@
 //     ascending by lane;
 //   * the output row is written by the lanes that hold it: one contiguous store per row.
 // A far-searching query therefore costs a few memory round trips per shell, not one per bin.
+// The tile kernel has already searched the first shells of every query it hands over: its list so
+// far sits in the query's output row and the first unsearched shell in slot 0 of the distance row,
+// so the search resumes there with a k-th best that already prunes most of the new shell.
 // Used for K-1 <= 64; larger K falls back to the one-lane-per-query list kernel.
 #pragma once
 #include "fg_query.hpp"
@@ -74,7 +77,17 @@ k_query_list_wave(QueryArgs a)
         const int32_t p = a.work_list[item];
         LaneGeom<D, DB> s;                          // identical in every lane
         s.init_geom(a, p);
-        uint64_t best = lane < kQueryBlock - cap ? 0ull : kEmptyKey;   // ascending by lane; low lanes pinned
+        const int32_t row = a.perm[p];
+        int32_t* oi = a.out_idx + (int64_t)row * a.k;
+        float* od = a.out_d2 + (int64_t)row * a.k;
+        uint64_t best = 0ull;                       // ascending by lane; low lanes pinned
+        if (lane >= kQueryBlock - cap) {
+            const int32_t j = lane - (kQueryBlock - cap) + 1;
+            const int32_t bi = oi[j];
+            best = bi < 0 ? kEmptyKey : (((uint64_t)__float_as_uint(od[j]) << 32) | (uint32_t)bi);
+        }
+        const int32_t R0 = __float_as_int(od[0]);
+        s.tau = __shfl(best, kQueryBlock - 1, 64);
         int32_t npend = 0, cand = 0;
 
         auto absorb64 = [&]() {                     // merges pend[0..min(npend,64)) into the best list
@@ -92,7 +105,7 @@ k_query_list_wave(QueryArgs a)
             __syncthreads();
         };
 
-        for (int32_t R = 0;; ++R) {   // ends at the latest when the cube covers the grid
+        for (int32_t R = R0;; ++R) {   // ends at the latest when the cube covers the grid
             const int32_t side = 2 * R + 1;
             int32_t ncols = 1;
 #pragma unroll
@@ -198,9 +211,6 @@ k_query_list_wave(QueryArgs a)
         }
 
         // output: slot 0 is the query itself, slot j >= 1 lives in lane 64 - cap + j - 1
-        const int32_t row = a.perm[p];
-        int32_t* oi = a.out_idx + (int64_t)row * a.k;
-        float* od = a.out_d2 + (int64_t)row * a.k;
         if (lane == 0) { oi[0] = row; od[0] = 0.0f; }
         if (lane >= kQueryBlock - cap) {
             const int32_t j = lane - (kQueryBlock - cap) + 1;

@@ -59,7 +59,7 @@ k_query_tile_sorted(QueryArgs a)
 
 #ifdef FG_TILE_PROF
     long long t_all = clock64(), t_setup = 0, t_stage = 0, t_scan = 0, t_absorb = 0, t_out = 0, tt;
-    int n_cols = 0, n_chunks = 0, n_iter = 0, n_absorb = 0, last_R = 0;
+    int n_cols = 0, n_chunks = 0, n_iter = 0, n_absorb = 0, last_R = 0, n_acc = 0;
 #define PROF_T0 tt = clock64();
 #define PROF_ADD(x) x += clock64() - tt;
 #else
@@ -82,11 +82,15 @@ k_query_tile_sorted(QueryArgs a)
         }
         net_sort<kPend>(pend);
         net_absorb<KC, kPend>(best, pend);
+#ifdef FG_TILE_PROF
+        n_acc += cnt;
+#endif
         cnt = 0;
         s.tau = best[KC - 1];
     };
 
-    for (int32_t R = 0;; ++R) {   // ends at the latest at R = n_bins - 1, when every lane's cube covers its grid
+    int32_t R = 0;
+    for (;; ++R) {   // ends at the latest at R = n_bins - 1, when every lane's cube covers its grid
         const int32_t side = 2 * R + 1;
         int32_t ncols = 1;
 #pragma unroll
@@ -259,7 +263,8 @@ k_query_tile_sorted(QueryArgs a)
         }
     }
 
-    // unfinished lanes go to the work list (wave-aggregated append)
+    // unfinished lanes go to the work list (wave-aggregated append); their lists so far leave with the
+    // finished rows, and the first shell still to search travels in slot 0 of the distance row
     const uint64_t mask = __ballot(active);
     if (mask) {
         int32_t base = 0;
@@ -275,7 +280,8 @@ k_query_tile_sorted(QueryArgs a)
     // two passes (indices, then distances) so the transposition needs KC x 64 words, not keys
     int32_t* rows_lds = reinterpret_cast<int32_t*>(lds64);
     uint32_t* dump = reinterpret_cast<uint32_t*>(lds64) + kQueryBlock;     // [KC][64] after the 64 row words
-    rows_lds[lane] = (valid && !active) ? (asks ? my_row : -2 - my_row) : -1;   // -1: nothing to write; <= -2: all-padding row
+    rows_lds[lane] = valid ? (asks ? my_row : -2 - my_row) : -1;   // -1: nothing to write; <= -2: all-padding row
+    const uint32_t resume_word = (uint32_t)(R + 1);
 #ifndef FG_TILE_PROF
     if (COUNT && valid) a.out_cand[my_row] = cand;
 #endif
@@ -302,6 +308,7 @@ k_query_tile_sorted(QueryArgs a)
             const int32_t row = enc >= 0 ? enc : -2 - enc;
             for (int32_t j = j0; j < k; j += kQueryBlock) {
                 uint32_t word = pass == 0 ? (enc >= 0 ? (uint32_t)row : 0xffffffffu) : 0u;   // slot 0: the row itself at distance 0
+                if (pass == 1 && ((mask >> ql) & 1)) word = resume_word;                     // handed over: where to resume
                 if (j > 0) word = dump[(KC - cap + j - 1) * kQueryBlock + ql];
                 if (pass == 0) a.out_idx[(int64_t)row * k + j] = (int32_t)word;
                 else a.out_d2[(int64_t)row * k + j] = __uint_as_float(word);
@@ -310,6 +317,8 @@ k_query_tile_sorted(QueryArgs a)
     }
 #ifdef FG_TILE_PROF
     PROF_ADD(t_out)
+    const int32_t pu_max = wave_max_i32(useful), pu_sum = wave_sum_i32(useful);
+    const int32_t pa_max = wave_max_i32(n_acc), pa_sum = wave_sum_i32(n_acc);
     if (COUNT && lane == 0 && (blockIdx.x + 1) * 64 <= a.n) {
         __syncthreads();
         int32_t* pr = a.out_cand + blockIdx.x * 64;   // debug build only: the tile's 64 count slots carry the profile
@@ -317,6 +326,7 @@ k_query_tile_sorted(QueryArgs a)
         pr[3] = (int32_t)(t_scan >> 4); pr[4] = (int32_t)(t_absorb >> 4); pr[5] = last_R; pr[6] = n_cols;
         pr[7] = n_chunks; pr[8] = n_iter; pr[9] = n_absorb; pr[10] = (int32_t)(t_out >> 4);
         pr[11] = __popcll(mask);
+        pr[12] = pu_max; pr[13] = pu_sum / 64; pr[14] = pa_max; pr[15] = pa_sum / 64;
     }
 #endif
 }

@@ -17,24 +17,37 @@ __host__ __device__ __forceinline__ void cmp_swap(uint64_t& lo, uint64_t& hi)
     hi = b;
 }
 
-// ascending bitonic sort of v[0..N), N a power of two
+// Batcher's odd-even merge: the N keys v[LO], v[LO+R], v[LO+2R], ... whose first and second halves are each
+// ascending become ascending.  N a power of two.  (N/2) log2(N) - N/2 + 1 comparators, fewer than the bitonic
+// merge's (N/2) log2(N).
+template <int LO, int N, int R, int M>
+__host__ __device__ __forceinline__ void net_oe_merge(uint64_t (&v)[M])
+{
+    if constexpr (N > 2) {
+        net_oe_merge<LO, N / 2, 2 * R>(v);
+        net_oe_merge<LO + R, N / 2, 2 * R>(v);
+#pragma unroll
+        for (int i = 1; i + 1 < N; i += 2) cmp_swap(v[LO + i * R], v[LO + (i + 1) * R]);
+    } else {
+        cmp_swap(v[LO], v[LO + R]);
+    }
+}
+
+template <int LO, int N, int M>
+__host__ __device__ __forceinline__ void net_oe_sort(uint64_t (&v)[M])
+{
+    if constexpr (N > 1) {
+        net_oe_sort<LO, N / 2>(v);
+        net_oe_sort<LO + N / 2, N / 2>(v);
+        net_oe_merge<LO, N, 1>(v);
+    }
+}
+
+// ascending sort of v[0..N), N a power of two (odd-even merge sort: 63 comparators for 16 keys)
 template <int N>
 __host__ __device__ __forceinline__ void net_sort(uint64_t (&v)[N])
 {
-#pragma unroll
-    for (int k = 2; k <= N; k <<= 1) {
-#pragma unroll
-        for (int j = k >> 1; j > 0; j >>= 1) {
-#pragma unroll
-            for (int i = 0; i < N; ++i) {
-                const int l = i ^ j;
-                if (l > i) {
-                    if ((i & k) == 0) cmp_swap(v[i], v[l]);
-                    else cmp_swap(v[l], v[i]);
-                }
-            }
-        }
-    }
+    net_oe_sort<0, N>(v);
 }
 
 // v[OFF..OFF+N) is bitonic -> ascending
@@ -68,21 +81,36 @@ __host__ __device__ __forceinline__ void net_absorb(uint64_t (&best)[KC], const 
         net_merge<KC, 0>(best);
     } else {
         net_merge<P, KC - P>(best);          // tail ascending
-        // head ascending + reversed tail is bitonic: merge on a renamed copy.  When KC is not a
-        // power of two the copy is padded in the middle with all-ones keys up to the next power
-        // of two (ascending head, plateau of maxima, descending tail is still bitonic); the
-        // padding is a compile-time constant, so every comparator that meets it folds away.
         constexpr int N = next_pow2(KC);
-        uint64_t w[N];
+        if constexpr (KC - P <= N / 2) {
+            // head and tail each ascending: odd-even merge of [head, padding | tail, padding], padded with
+            // all-ones keys up to the next power of two.  The padding is a compile-time constant, so every
+            // comparator that meets it folds away (65 comparators remain for 16 + 16 keys, 113 for 32 + 16).
+            uint64_t w[N];
 #pragma unroll
-        for (int i = 0; i < KC - P; ++i) w[i] = best[i];
+            for (int i = 0; i < N; ++i) w[i] = ~0ull;
 #pragma unroll
-        for (int i = KC - P; i < N - P; ++i) w[i] = ~0ull;
+            for (int i = 0; i < KC - P; ++i) w[i] = best[i];
 #pragma unroll
-        for (int i = 0; i < P; ++i) w[N - P + i] = best[KC - 1 - i];
-        net_merge<N, 0>(w);
+            for (int i = 0; i < P; ++i) w[N / 2 + i] = best[KC - P + i];
+            net_oe_merge<0, N, 1>(w);
 #pragma unroll
-        for (int i = 0; i < KC; ++i) best[i] = w[i];
+            for (int i = 0; i < KC; ++i) best[i] = w[i];
+        } else {
+            // head ascending + reversed tail is bitonic: merge on a renamed copy.  When KC is not a
+            // power of two the copy is padded in the middle with all-ones keys (ascending head, plateau
+            // of maxima, descending tail is still bitonic); the padding folds away as above.
+            uint64_t w[N];
+#pragma unroll
+            for (int i = 0; i < KC - P; ++i) w[i] = best[i];
+#pragma unroll
+            for (int i = KC - P; i < N - P; ++i) w[i] = ~0ull;
+#pragma unroll
+            for (int i = 0; i < P; ++i) w[N - P + i] = best[KC - 1 - i];
+            net_merge<N, 0>(w);
+#pragma unroll
+            for (int i = 0; i < KC; ++i) best[i] = w[i];
+        }
     }
 }
 
