@@ -20,6 +20,7 @@
 // Used for K-1 <= 64; larger K falls back to the one-lane-per-query list kernel.
 #pragma once
 #include "fg_query.hpp"
+#include "fg_sortnet.hpp"
 
 namespace fg {
 
@@ -27,9 +28,7 @@ __device__ __forceinline__ uint64_t wave_sort_step(uint64_t v, int lane, int k, 
 {
     const uint64_t other = __shfl_xor(v, j, 64);
     const bool keep_min = ((lane & k) == 0) == ((lane & j) == 0);
-    const uint64_t mn = other < v ? other : v;
-    const uint64_t mx = other < v ? v : other;
-    return keep_min ? mn : mx;
+    return keep_min ? key_min(v, other) : key_max(v, other);
 }
 
 // ascending (by lane) bitonic sort of one key per lane
@@ -99,7 +98,7 @@ k_query_list_wave(QueryArgs a)
             npend -= take;
             v = wave_sort64(v, lane);
             const uint64_t rv = __shfl(v, kQueryBlock - 1 - lane, 64);
-            best = rv < best ? rv : best;
+            best = key_min(rv, best);
             best = wave_merge64(best, lane);
             s.tau = __shfl(best, kQueryBlock - 1, 64);
             __syncthreads();
