@@ -44,7 +44,10 @@ k_query_tile_sorted(QueryArgs a)
     //      [rows 64 words][KC x 64 words of the sorted lists, indices first, distances second]
     extern __shared__ uint64_t lds64[];
     const int lane = threadIdx.x;
-    uint64_t* pend_lds = lds64 + lane;
+    // pending keys: index words [kPend][64], then distance words [kPend][64]
+    uint32_t* const pend_lds = reinterpret_cast<uint32_t*>(lds64) + lane;
+    constexpr int kPendHalf = kPend * kQueryBlock;
+    uint32_t* pend_top = pend_lds;        // next free slot of this lane
     constexpr int NV = stage_vecs<D>();
     float4* stage = reinterpret_cast<float4*>(lds64 + kPend * kQueryBlock);   // [kStageChunk][NV]
 
@@ -69,15 +72,16 @@ k_query_tile_sorted(QueryArgs a)
     uint64_t best[KC];
 #pragma unroll
     for (int i = 0; i < KC; ++i) best[i] = (i < KC - cap) ? 0ull : kEmptyKey;
-    int32_t cnt = 0, cand = 0;
+    int32_t cand = 0;
     int32_t useful = 0;   // candidates this lane evaluated
     int32_t passes = 0;   // scan passes of the wave (kUnroll lane slots each)
 
     auto absorb = [&]() {
         uint64_t pend[kPend];
+        const int32_t cnt = (int32_t)(pend_top - pend_lds) / kQueryBlock;
 #pragma unroll
         for (int i = 0; i < kPend; ++i) {
-            const uint64_t v = pend_lds[i * kQueryBlock];
+            const uint64_t v = ((uint64_t)pend_lds[kPendHalf + i * kQueryBlock] << 32) | pend_lds[i * kQueryBlock];
             pend[i] = i < cnt ? v : kEmptyKey;
         }
         net_sort<kPend>(pend);
@@ -85,11 +89,12 @@ k_query_tile_sorted(QueryArgs a)
 #ifdef FG_TILE_PROF
         n_acc += cnt;
 #endif
-        cnt = 0;
+        pend_top = pend_lds;
         s.tau = best[KC - 1];
     };
 
     int32_t R = 0;
+    const uint32_t* const pend_full = pend_lds + (kPend - kUnroll) * kQueryBlock;   // beyond this a pass may overflow
     for (;; ++R) {   // ends at the latest at R = n_bins - 1, when every lane's cube covers its grid
         const int32_t side = 2 * R + 1;
         int32_t ncols = 1;
@@ -142,6 +147,7 @@ k_query_tile_sorted(QueryArgs a)
                     }
                     a1 = a.bounds[row + za];
                     b1 = a.bounds[row + zb + 1];
+                    if (R == 0) { a2 = p + 1; b2 = b1; b1 = p; }   // the query's own bin, the query itself left out
                 } else {
                     if (cz - R >= 0) {
                         const float g = s.gap(DB - 1, cz - R, -R);
@@ -207,6 +213,7 @@ k_query_tile_sorted(QueryArgs a)
                     const int32_t rem = e - q;
                     if (!__any(rem > 0)) break;
                     float w[kUnroll][NV * 4];
+                    const uint32_t tau_hi = (uint32_t)(s.tau >> 32);
                     const int32_t i0 = rem > 0 ? q - base : 0;       // reads past the lane's range stay inside the padded chunk
 #pragma unroll
                     for (int u = 0; u < kUnroll; ++u) {
@@ -225,29 +232,31 @@ k_query_tile_sorted(QueryArgs a)
                             diff = s.x[c] - w[u][c];
                             d2 = d2 + diff * diff;
                         }
-                        const bool live = u < rem && q + u != p;
+                        const bool live = u < rem;
                         if (COUNT) cand += live;
+                        // kept if its distance does not exceed the k-th best's (a tie on the distance may lose
+                        // on the index: the merge decides); NaN (poisoned) patterns lie above every bound
                         const uint32_t bits = __float_as_uint(d2);
-                        const uint64_t key = ((uint64_t)bits << 32) | (uint32_t)__float_as_int(w[u][D]);
-                        if (live && key < s.tau) {
-                            pend_lds[cnt * kQueryBlock] = key;
-                            ++cnt;
+                        if (live && bits <= tau_hi) {
+                            pend_top[0] = __float_as_uint(w[u][D]);
+                            pend_top[kPendHalf] = bits;
+                            pend_top += kQueryBlock;
                         }
                     }
                     q += kUnroll;
                     ++passes;
 #ifdef FG_TILE_PROF
                     ++n_iter;
-                    if (__any(cnt > kPend - kUnroll)) { long long t2 = clock64(); absorb(); t_absorb += clock64() - t2; ++n_absorb; }
+                    if (__any(pend_top > pend_full)) { long long t2 = clock64(); absorb(); t_absorb += clock64() - t2; ++n_absorb; }
 #else
-                    if (__any(cnt > kPend - kUnroll)) absorb();
+                    if (__any(pend_top > pend_full)) absorb();
 #endif
                 }
                 PROF_ADD(t_scan)
             }
         }
         PROF_T0
-        if (__any(cnt > 0)) absorb();
+        if (__any(pend_top != pend_lds)) absorb();
         PROF_ADD(t_absorb)
         if (active && s.certified(R)) active = false;
         const int32_t n_active = __popcll(__ballot(active));
