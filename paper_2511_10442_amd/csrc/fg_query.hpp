@@ -24,7 +24,10 @@
 namespace fg {
 
 constexpr int kQueryBlock = 64;                    // one wavefront per workgroup
-constexpr int kStageChunk = 256;                  // points staged through LDS per chunk (tile kernel)
+#ifndef FG_STAGE_CHUNK
+#define FG_STAGE_CHUNK 256
+#endif
+constexpr int kStageChunk = FG_STAGE_CHUNK;       // points staged through LDS per chunk (tile kernel)
 constexpr float kBoundShrink = 0.99999618530273f;  // 1 - 2^-18: covers fp32 rounding of d2 and of the bound
 
 // Per-lane geometry of one query: its coordinates, its bin, its row split's grid, and the
