@@ -5,10 +5,13 @@
 //   prepare   zero the bin counters, reset the bounding-box keys
 //   bbox      per row split, min/max of the first d_bin coordinates (register, wave and block
 //             reduction, one atomic pair per block and dimension on an order-preserving key)
-//   geometry  per (row split, dim): lower edge, bins per unit length, bin width, rounding slack
-//   assign    flat bin of every point + its arrival rank inside the bin (LDS-privatised
-//             histogram per block, one returning global atomic per distinct bin and block)
-//   scan      exclusive prefix over the counters (partials / tops / apply)
+//   assign    per (row split, dim) the grid geometry (lower edge, bins per unit length, bin width,
+//             rounding slack: computed from the bounding box where needed, the records written
+//             for the query kernels); flat bin of every point + its arrival rank inside the bin
+//             (LDS-privatised histogram per block, one returning global atomic per distinct bin
+//             and block)
+//   scan      exclusive prefix over the counters (per-chunk totals, then apply; a pass over the
+//             totals in between only when there are many chunks)
 //   scatter   sorted position = bounds[bin] + rank: write perm and the bin-ordered SoA coords
 #include "fg_internal.hpp"
 
@@ -54,7 +57,7 @@ __device__ __forceinline__ float wave_max(float v)
 // (the common case) is reduced in registers, then across the wave, then across the block, and
 // issues one atomic pair per dimension; a chunk straddling a split boundary falls back to
 // per-wave or per-lane atomics.  Same-address atomics serialise, so their number matters.
-constexpr int kBboxItems = 16;
+constexpr int kBboxItems = 4;     // few points per thread: the launch needs well over 256 blocks to keep loads in flight
 constexpr int kBboxChunk = kBlock * kBboxItems;
 
 template <int DB>
@@ -131,17 +134,16 @@ k_bbox(const float* __restrict__ coords, const int32_t* __restrict__ row_splits,
 //           the row split lands in bin 0 (zero, denormal-small or non-finite extent, empty split).
 //   slack  bounds |true bin threshold - (lo + j*w)| from above: the float32 evaluation of
 //           floor((x-lo)*inv_w) and of lo + j*w together err by < 2^-21 * max(|lo|,|hi|,hi-lo).
-__global__ void __launch_bounds__(kBlock)
-k_geometry(const uint32_t* __restrict__ bbox_keys, int32_t n_keys, int32_t n_bins, float* __restrict__ geom)
+struct DimGeom { float lo, inv_w, w, slack; };
+
+__device__ __forceinline__ DimGeom dim_geometry(const uint32_t* __restrict__ bbox_keys, int32_t n_keys, int32_t t, int32_t n_bins)
 {
-    int32_t t = blockIdx.x * kBlock + threadIdx.x;
-    if (t >= n_keys) return;
     float lo = key_to_float(bbox_keys[t]);
-    float hi = key_to_float(bbox_keys[n_keys + t]);
-    float ext = hi - lo;
+    const float hi = key_to_float(bbox_keys[n_keys + t]);
+    const float ext = hi - lo;
     float inv_w = 0.0f, w = 0.0f, slack = 0.0f;
     if (ext >= 1e-30f && ext <= 3.0e38f) {          // false for NaN and for the empty-split sentinels
-        float iw = (float)n_bins / ext;
+        const float iw = (float)n_bins / ext;
         if (iw <= 3.0e38f) {
             inv_w = iw;
             w = ext / (float)n_bins;
@@ -149,8 +151,7 @@ k_geometry(const uint32_t* __restrict__ bbox_keys, int32_t n_keys, int32_t n_bin
         }
     }
     if (!(lo >= -3.0e38f && lo <= 3.0e38f)) lo = 0.0f;   // empty split: keep the record finite
-    float* g = geom + (int64_t)t * kGeomStride;
-    g[0] = lo; g[1] = inv_w; g[2] = w; g[3] = slack;
+    return DimGeom{lo, inv_w, w, slack};
 }
 
 // Bin of every point and its arrival rank inside the bin.  The rank comes from an atomic add on
@@ -169,9 +170,17 @@ template <int DB>
 __global__ void __launch_bounds__(kBlock)
 k_assign(const float* __restrict__ coords, const int32_t* __restrict__ row_splits, int32_t n, int32_t d,
          int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, int32_t morton_bits,
-         const float* __restrict__ geom, int32_t* __restrict__ bin_idx, int32_t* __restrict__ rank,
-         int32_t* __restrict__ counters)
+         const uint32_t* __restrict__ bbox_keys, float* __restrict__ geom, int32_t* __restrict__ bin_idx,
+         int32_t* __restrict__ rank, int32_t* __restrict__ counters)
 {
+    // the geometry records the query kernels read: written here by the first blocks; the bins below are
+    // computed from the same bounding-box keys with the same arithmetic
+    const int32_t n_keys = n_segments * DB;
+    for (int32_t t = blockIdx.x * kBlock + threadIdx.x; t < n_keys; t += gridDim.x * kBlock) {
+        const DimGeom r = dim_geometry(bbox_keys, n_keys, t, n_bins);
+        float* g = geom + (int64_t)t * kGeomStride;
+        g[0] = r.lo; g[1] = r.inv_w; g[2] = r.w; g[3] = r.slack;
+    }
     __shared__ int32_t keys[kAssignSlots];
     __shared__ int32_t cnts[kAssignSlots];     // block-local population, then the block's base in the bin
     for (int i = threadIdx.x; i < kAssignSlots; i += kBlock) { keys[i] = -1; cnts[i] = 0; }
@@ -184,16 +193,17 @@ k_assign(const float* __restrict__ coords, const int32_t* __restrict__ row_split
         if (i >= n) continue;
         const int32_t s = segment_of(row_splits, n_segments, (int32_t)i);
         const float* p = coords + i * d;
-        const float* g = geom + (int64_t)s * DB * kGeomStride;
+        int32_t cell[DB];
+#pragma unroll
+        for (int c = 0; c < DB; ++c) {
+            const DimGeom r = dim_geometry(bbox_keys, n_keys, s * DB + c, n_bins);
+            cell[c] = cell_of(p[c], r.lo, r.inv_w, n_bins);
+        }
         int32_t f = 0;
         if (morton_bits == 0) {                 // row-major, last dimension fastest (what the query kernels expect)
 #pragma unroll
-            for (int c = 0; c < DB; ++c)
-                f = f * n_bins + cell_of(p[c], g[c * kGeomStride + 0], g[c * kGeomStride + 1], n_bins);
+            for (int c = 0; c < DB; ++c) f = f * n_bins + cell[c];
         } else {                                // bit-interleaved: consecutive bins form compact blocks in space
-            int32_t cell[DB];
-#pragma unroll
-            for (int c = 0; c < DB; ++c) cell[c] = cell_of(p[c], g[c * kGeomStride + 0], g[c * kGeomStride + 1], n_bins);
             for (int b = 0; b < morton_bits; ++b) {
 #pragma unroll
                 for (int c = 0; c < DB; ++c) f |= ((cell[c] >> b) & 1) << (b * DB + (DB - 1 - c));
@@ -286,9 +296,20 @@ k_scan_tops(int32_t* __restrict__ partials, int32_t n_partials)
     }
 }
 
+// partials hold exclusive prefixes (after k_scan_tops) or, with totals = true, the raw per-chunk totals, of
+// which every block then sums those before its own (cheaper than a third launch while there are few chunks)
+template <bool TOTALS>
 __global__ void __launch_bounds__(kBlock)
 k_scan_apply(int32_t* __restrict__ counters, int64_t n_counters, const int32_t* __restrict__ partials)
 {
+    int32_t chunk_base;
+    if (TOTALS) {
+        int32_t part = 0;
+        for (int32_t q = threadIdx.x; q < (int32_t)blockIdx.x; q += kBlock) part += partials[q];
+        block_excl_scan(part, &chunk_base);
+    } else {
+        chunk_base = partials[blockIdx.x];
+    }
     int64_t base = (int64_t)blockIdx.x * kScanChunk + (int64_t)threadIdx.x * kScanItems;
     int32_t v[kScanItems];
     int32_t sum = 0;
@@ -299,7 +320,7 @@ k_scan_apply(int32_t* __restrict__ counters, int64_t n_counters, const int32_t* 
         sum += v[j];
     }
     int32_t total;
-    int32_t run = block_excl_scan(sum, &total) + partials[blockIdx.x];
+    int32_t run = block_excl_scan(sum, &total) + chunk_base;
 #pragma unroll
     for (int j = 0; j < kScanItems; ++j) {
         int64_t q = base + j;
@@ -327,7 +348,7 @@ template <int DB>
 static void launch_bbox_assign(bool assign, const float* coords, const int32_t* row_splits, int32_t n, int32_t d,
                                int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, int32_t morton_bits,
                                uint32_t* bbox_keys,
-                               const float* geom, int32_t* bin_idx, int32_t* rank, int32_t* counters,
+                               float* geom, int32_t* bin_idx, int32_t* rank, int32_t* counters,
                                hipStream_t stream)
 {
     if (!assign)
@@ -335,8 +356,8 @@ static void launch_bbox_assign(bool assign, const float* coords, const int32_t* 
                            row_splits, n, d, n_segments, bbox_keys);
     else
         hipLaunchKernelGGL(k_assign<DB>, dim3((n + kAssignChunk - 1) / kAssignChunk), dim3(kBlock), 0, stream, coords,
-                           row_splits, n, d, n_segments, n_bins, cells_per_segment, morton_bits, geom, bin_idx, rank,
-                           counters);
+                           row_splits, n, d, n_segments, n_bins, cells_per_segment, morton_bits, bbox_keys, geom,
+                           bin_idx, rank, counters);
 }
 
 template <int D>
@@ -377,17 +398,20 @@ hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_
         default: return hipErrorInvalidValue;                                                                      \
     }
     FG_DB_SWITCH(false)
-    hipLaunchKernelGGL(k_geometry, dim3((n_keys + kBlock - 1) / kBlock), dim3(kBlock), 0, stream, bbox_keys, n_keys,
-                       n_bins, geom);
     FG_DB_SWITCH(true)
 #undef FG_DB_SWITCH
     {
         int64_t n_chunks = (n_counters + kScanChunk - 1) / kScanChunk;
         hipLaunchKernelGGL(k_scan_partials, dim3((unsigned)n_chunks), dim3(kBlock), 0, stream, bounds, n_counters,
                            scan_partials);
-        hipLaunchKernelGGL(k_scan_tops, dim3(1), dim3(kBlock), 0, stream, scan_partials, (int32_t)n_chunks);
-        hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)n_chunks), dim3(kBlock), 0, stream, bounds, n_counters,
-                           scan_partials);
+        if (n_chunks <= 2048) {
+            hipLaunchKernelGGL(k_scan_apply<true>, dim3((unsigned)n_chunks), dim3(kBlock), 0, stream, bounds, n_counters,
+                               scan_partials);
+        } else {
+            hipLaunchKernelGGL(k_scan_tops, dim3(1), dim3(kBlock), 0, stream, scan_partials, (int32_t)n_chunks);
+            hipLaunchKernelGGL(k_scan_apply<false>, dim3((unsigned)n_chunks), dim3(kBlock), 0, stream, bounds, n_counters,
+                               scan_partials);
+        }
     }
     switch (d) {
         case 2: launch_scatter<2>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
