@@ -70,12 +70,13 @@ Layout make_layout(int64_t n, int32_t d, int32_t n_segments, int32_t n_bins, int
     L.total_bins = cells * n_segments;
     L.soa_stride = (n + 63) / 64 * 64;
     size_t off = 0;
-    L.keys = off;     off = align_up(off + sizeof(uint32_t) * 2 * (size_t)n_segments * d_bin);
+    L.keys = off;     off = align_up(off + sizeof(uint32_t) * 2 * (size_t)n_segments * d_bin * kKeyStride);
     L.geom = off;     off = align_up(off + sizeof(float) * kGeomStride * (size_t)n_segments * d_bin);
     L.bin_idx = off;  off = align_up(off + sizeof(int32_t) * (size_t)n);
     L.rank = off;     off = align_up(off + sizeof(int32_t) * (size_t)n);
     L.perm = off;     off = align_up(off + sizeof(int32_t) * (size_t)n);
-    L.soa = off;      off = align_up(off + sizeof(float) * (size_t)L.soa_stride * d);
+    // d = 3: room for four floats per point, because the backward keeps a padded copy of the rows here
+    L.soa = off;      off = align_up(off + sizeof(float) * (size_t)L.soa_stride * (d == 3 ? 4 : d));
     L.bounds = off;   off = align_up(off + sizeof(int32_t) * (size_t)(L.total_bins + 1));
     L.partials = off; off = align_up(off + sizeof(int32_t) * (size_t)((L.total_bins + 1 + kScanChunkHost - 1) / kScanChunkHost));
     L.work_list = off; off = align_up(off + sizeof(int32_t) * (size_t)n);
@@ -328,6 +329,7 @@ fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float*
     if (n == 0) return FG_OK;
     if (!grad_d2 || !idx || !coords || !grad_coords) return FG_ERR_NULL;
     const int32_t* perm = nullptr;
+    const float* coords4 = nullptr;
     if (row_splits && workspace && n_segments >= 1) {
         // bin the points once more to get a spatially coherent row order (the forward's workspace
         // is scratch by contract, so nothing of it is assumed to survive)
@@ -341,8 +343,9 @@ fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float*
                              stream);
         if (st != FG_OK) return st;
         perm = view.perm;
+        if (d == 3) coords4 = view.sorted_soa;    // in this mode: the rows padded to four floats, original order
     }
-    hipError_t e = launch_backward(grad_d2, idx, coords, perm, (int32_t)n, d, k, grad_coords, (hipStream_t)stream);
+    hipError_t e = launch_backward(grad_d2, idx, coords, coords4, perm, (int32_t)n, d, k, grad_coords, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }
 

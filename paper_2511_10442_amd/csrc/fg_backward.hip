@@ -85,10 +85,40 @@ __device__ __forceinline__ void bwd_insert(int32_t* keys, float* vals, int32_t u
     for (int c = 0; c < D; ++c) atomicAdd(&grad_coords[(int64_t)u * D + c], t[c]);
 }
 
-template <int D>
+// One point's coordinates with as few load instructions as its row allows: the gathers of the
+// neighbours' coordinates are a third of this kernel's time when issued one float at a time.
+// VEC promises a 16-byte aligned coords pointer.  For D = 3 the rows come from a copy padded to
+// four floats (coords4), made while the rows were binned.
+template <int D, bool VEC>
+__device__ __forceinline__ void load_point(const float* __restrict__ coords, const float4* __restrict__ coords4,
+                                           int64_t r, float (&out)[D])
+{
+    if constexpr (D == 3) {
+        if (coords4) {
+            const float4 f = coords4[r];
+            out[0] = f.x; out[1] = f.y; out[2] = f.z;
+            return;
+        }
+    }
+    if constexpr (VEC && D % 4 == 0) {
+        const float4* p = reinterpret_cast<const float4*>(coords) + r * (D / 4);
+#pragma unroll
+        for (int q = 0; q < D / 4; ++q) { const float4 f = p[q]; out[4 * q] = f.x; out[4 * q + 1] = f.y; out[4 * q + 2] = f.z; out[4 * q + 3] = f.w; }
+    } else if constexpr (VEC && D % 2 == 0) {
+        const float2* p = reinterpret_cast<const float2*>(coords) + r * (D / 2);
+#pragma unroll
+        for (int q = 0; q < D / 2; ++q) { const float2 f = p[q]; out[2 * q] = f.x; out[2 * q + 1] = f.y; }
+    } else {
+#pragma unroll
+        for (int c = 0; c < D; ++c) out[c] = coords[r * D + c];
+    }
+}
+
+template <int D, bool VEC>
 __global__ void __launch_bounds__(kBwdBlock)
 k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ idx, const float* __restrict__ coords,
-                 const int32_t* __restrict__ perm, int32_t n, int32_t k, float* __restrict__ grad_coords)
+                 const float4* __restrict__ coords4, const int32_t* __restrict__ perm, int32_t n, int32_t k,
+                 float* __restrict__ grad_coords)
 {
     constexpr int SLOTS = bwd_slots<D>();
     constexpr int ROWS = bwd_rows<D>();
@@ -106,17 +136,19 @@ k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ 
         const bool live = pos < n;                   // whole 16-lane groups are live or dead together
         const int32_t v = live ? perm[pos] : 0;
         float xv[D], acc[D];
+        load_point<D, VEC>(coords, coords4, v, xv);     // dead groups read row 0: harmless
 #pragma unroll
-        for (int c = 0; c < D; ++c) { xv[c] = live ? coords[(int64_t)v * D + c] : 0.0f; acc[c] = 0.0f; }
+        for (int c = 0; c < D; ++c) acc[c] = 0.0f;
         if (live) {
             for (int32_t j = l; j < k; j += kLanesPerRow) {
                 const int32_t u = idx[(int64_t)v * k + j];
                 if (u < 0 || u >= n || u == v) continue;   // padding / out of range: ignored; self contributes exactly 0
                 const float g2 = 2.0f * grad_d2[(int64_t)v * k + j];
-                float t[D];
+                float t[D], xu[D];
+                load_point<D, VEC>(coords, coords4, u, xu);
 #pragma unroll
                 for (int c = 0; c < D; ++c) {
-                    const float tc = g2 * (xv[c] - coords[(int64_t)u * D + c]);
+                    const float tc = g2 * (xv[c] - xu[c]);
                     acc[c] += tc;
                     t[c] = -tc;
                 }
@@ -142,12 +174,16 @@ k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ 
 }
 
 template <int D>
-static void launch_bwd_tiled(const float* grad_d2, const int32_t* idx, const float* coords, const int32_t* perm,
-                             int32_t n, int32_t k, float* grad_coords, hipStream_t stream)
+static void launch_bwd_tiled(const float* grad_d2, const int32_t* idx, const float* coords, const float4* coords4,
+                             const int32_t* perm, int32_t n, int32_t k, float* grad_coords, hipStream_t stream)
 {
     unsigned grid = (unsigned)((n + bwd_rows<D>() - 1) / bwd_rows<D>());
-    hipLaunchKernelGGL(k_backward_tiled<D>, dim3(grid), dim3(kBwdBlock), 0, stream, grad_d2, idx, coords, perm, n, k,
-                       grad_coords);
+    if (((uintptr_t)coords % 16) == 0)
+        hipLaunchKernelGGL((k_backward_tiled<D, true>), dim3(grid), dim3(kBwdBlock), 0, stream, grad_d2, idx, coords,
+                           coords4, perm, n, k, grad_coords);
+    else
+        hipLaunchKernelGGL((k_backward_tiled<D, false>), dim3(grid), dim3(kBwdBlock), 0, stream, grad_d2, idx, coords,
+                           coords4, perm, n, k, grad_coords);
 }
 
 template <int D>
@@ -159,8 +195,8 @@ static void launch_bwd(const float* grad_d2, const int32_t* idx, const float* co
     hipLaunchKernelGGL(k_backward<D>, dim3(grid), dim3(kBwdBlock), 0, stream, grad_d2, idx, coords, n, k, grad_coords);
 }
 
-hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, const int32_t* perm,
-                           int32_t n, int32_t d, int32_t k, float* grad_coords, hipStream_t stream)
+hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, const float* coords4,
+                           const int32_t* perm, int32_t n, int32_t d, int32_t k, float* grad_coords, hipStream_t stream)
 {
     {
         int64_t total = (int64_t)n * d;
@@ -170,15 +206,15 @@ hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float
     }
     if (perm) {
         switch (d) {
-            case 2: launch_bwd_tiled<2>(grad_d2, idx, coords, perm, n, k, grad_coords, stream); break;
-            case 3: launch_bwd_tiled<3>(grad_d2, idx, coords, perm, n, k, grad_coords, stream); break;
-            case 4: launch_bwd_tiled<4>(grad_d2, idx, coords, perm, n, k, grad_coords, stream); break;
-            case 5: launch_bwd_tiled<5>(grad_d2, idx, coords, perm, n, k, grad_coords, stream); break;
-            case 6: launch_bwd_tiled<6>(grad_d2, idx, coords, perm, n, k, grad_coords, stream); break;
-            case 7: launch_bwd_tiled<7>(grad_d2, idx, coords, perm, n, k, grad_coords, stream); break;
-            case 8: launch_bwd_tiled<8>(grad_d2, idx, coords, perm, n, k, grad_coords, stream); break;
-            case 9: launch_bwd_tiled<9>(grad_d2, idx, coords, perm, n, k, grad_coords, stream); break;
-            case 10: launch_bwd_tiled<10>(grad_d2, idx, coords, perm, n, k, grad_coords, stream); break;
+            case 2: launch_bwd_tiled<2>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
+            case 3: launch_bwd_tiled<3>(grad_d2, idx, coords, reinterpret_cast<const float4*>(coords4), perm, n, k, grad_coords, stream); break;
+            case 4: launch_bwd_tiled<4>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
+            case 5: launch_bwd_tiled<5>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
+            case 6: launch_bwd_tiled<6>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
+            case 7: launch_bwd_tiled<7>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
+            case 8: launch_bwd_tiled<8>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
+            case 9: launch_bwd_tiled<9>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
+            case 10: launch_bwd_tiled<10>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
             default: return hipErrorInvalidValue;
         }
         return hipGetLastError();

@@ -39,7 +39,7 @@ k_prepare(int32_t* __restrict__ counters, int64_t n_counters, uint32_t* __restri
     int64_t step = (int64_t)gridDim.x * kBlock;
     for (int64_t j = i; j < n_counters; j += step) counters[j] = 0;
     // keys: [S][d_bin] minima then [S][d_bin] maxima
-    for (int64_t j = i; j < 2 * (int64_t)n_keys; j += step) bbox_keys[j] = (j < n_keys) ? 0xffffffffu : 0u;
+    for (int64_t j = i; j < 2 * (int64_t)n_keys; j += step) bbox_keys[j * kKeyStride] = (j < n_keys) ? 0xffffffffu : 0u;
 }
 
 __device__ __forceinline__ float wave_min(float v)
@@ -69,7 +69,7 @@ k_bbox(const float* __restrict__ coords, const int32_t* __restrict__ row_splits,
     const int64_t base = (int64_t)blockIdx.x * kBboxChunk;
     const int32_t last = (int32_t)(base + kBboxChunk < n ? base + kBboxChunk : n) - 1;
     uint32_t* kmin = bbox_keys;
-    uint32_t* kmax = bbox_keys + (int64_t)n_segments * DB;
+    uint32_t* kmax = bbox_keys + (int64_t)n_segments * DB * kKeyStride;
     const int32_t s_first = segment_of(row_splits, n_segments, (int32_t)base);
     const int32_t s_last = segment_of(row_splits, n_segments, last);
     if (s_first == s_last) {
@@ -99,8 +99,8 @@ k_bbox(const float* __restrict__ coords, const int32_t* __restrict__ row_splits,
             float a = red[0][0][c], b = red[1][0][c];
 #pragma unroll
             for (int w = 1; w < kBlock / 64; ++w) { a = fminf(a, red[0][w][c]); b = fmaxf(b, red[1][w][c]); }
-            atomicMin(&kmin[s_first * DB + c], float_to_key(a));
-            atomicMax(&kmax[s_first * DB + c], float_to_key(b));
+            atomicMin(&kmin[(s_first * DB + c) * kKeyStride], float_to_key(a));
+            atomicMax(&kmax[(s_first * DB + c) * kKeyStride], float_to_key(b));
         }
         return;
     }
@@ -118,12 +118,12 @@ k_bbox(const float* __restrict__ coords, const int32_t* __restrict__ row_splits,
             if (uniform) {
                 const float a = wave_min(x), b = wave_max(x);   // dead lanes duplicate the chunk's last point: harmless
                 if ((threadIdx.x & 63) == 0) {
-                    atomicMin(&kmin[s * DB + c], float_to_key(a));
-                    atomicMax(&kmax[s * DB + c], float_to_key(b));
+                    atomicMin(&kmin[(s * DB + c) * kKeyStride], float_to_key(a));
+                    atomicMax(&kmax[(s * DB + c) * kKeyStride], float_to_key(b));
                 }
             } else if (live) {
-                atomicMin(&kmin[s * DB + c], float_to_key(x));
-                atomicMax(&kmax[s * DB + c], float_to_key(x));
+                atomicMin(&kmin[(s * DB + c) * kKeyStride], float_to_key(x));
+                atomicMax(&kmax[(s * DB + c) * kKeyStride], float_to_key(x));
             }
         }
     }
@@ -138,8 +138,8 @@ struct DimGeom { float lo, inv_w, w, slack; };
 
 __device__ __forceinline__ DimGeom dim_geometry(const uint32_t* __restrict__ bbox_keys, int32_t n_keys, int32_t t, int32_t n_bins)
 {
-    float lo = key_to_float(bbox_keys[t]);
-    const float hi = key_to_float(bbox_keys[n_keys + t]);
+    float lo = key_to_float(bbox_keys[(int64_t)t * kKeyStride]);
+    const float hi = key_to_float(bbox_keys[(int64_t)(n_keys + t) * kKeyStride]);
     const float ext = hi - lo;
     float inv_w = 0.0f, w = 0.0f, slack = 0.0f;
     if (ext >= 1e-30f && ext <= 3.0e38f) {          // false for NaN and for the empty-split sentinels
@@ -329,7 +329,10 @@ k_scan_apply(int32_t* __restrict__ counters, int64_t n_counters, const int32_t* 
     }
 }
 
-template <int D>
+// ROWS_ONLY (the backward's row order): no bin-ordered coordinates; for D = 3 the soa area instead
+// receives the rows in their original order padded to four floats, which the backward kernel gathers
+// with one load per neighbour.
+template <int D, bool ROWS_ONLY>
 __global__ void __launch_bounds__(kBlock)
 k_scatter(const float* __restrict__ coords, int32_t n, const int32_t* __restrict__ bin_idx,
           const int32_t* __restrict__ rank, const int32_t* __restrict__ bounds,
@@ -340,8 +343,12 @@ k_scatter(const float* __restrict__ coords, int32_t n, const int32_t* __restrict
     int32_t pos = bounds[bin_idx[i]] + rank[i];
     perm[pos] = i;
     const float* p = coords + (int64_t)i * D;
+    if constexpr (ROWS_ONLY) {
+        if constexpr (D == 3) reinterpret_cast<float4*>(soa)[i] = make_float4(p[0], p[1], p[2], 0.0f);
+    } else {
 #pragma unroll
-    for (int c = 0; c < D; ++c) soa[(int64_t)c * soa_stride + pos] = p[c];
+        for (int c = 0; c < D; ++c) soa[(int64_t)c * soa_stride + pos] = p[c];
+    }
 }
 
 template <int DB>
@@ -361,12 +368,16 @@ static void launch_bbox_assign(bool assign, const float* coords, const int32_t* 
 }
 
 template <int D>
-static void launch_scatter(const float* coords, int32_t n, const int32_t* bin_idx, const int32_t* rank,
+static void launch_scatter(bool rows_only, const float* coords, int32_t n, const int32_t* bin_idx, const int32_t* rank,
                            const int32_t* bounds, int32_t* perm, float* soa, int64_t soa_stride, hipStream_t stream)
 {
     int grid = (n + kBlock - 1) / kBlock;
-    hipLaunchKernelGGL(k_scatter<D>, dim3(grid), dim3(kBlock), 0, stream, coords, n, bin_idx, rank, bounds, perm, soa,
-                       soa_stride);
+    if (rows_only)
+        hipLaunchKernelGGL((k_scatter<D, true>), dim3(grid), dim3(kBlock), 0, stream, coords, n, bin_idx, rank, bounds,
+                           perm, soa, soa_stride);
+    else
+        hipLaunchKernelGGL((k_scatter<D, false>), dim3(grid), dim3(kBlock), 0, stream, coords, n, bin_idx, rank, bounds,
+                           perm, soa, soa_stride);
 }
 
 hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_t n, int32_t d,
@@ -414,15 +425,15 @@ hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_
         }
     }
     switch (d) {
-        case 2: launch_scatter<2>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
-        case 3: launch_scatter<3>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
-        case 4: launch_scatter<4>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
-        case 5: launch_scatter<5>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
-        case 6: launch_scatter<6>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
-        case 7: launch_scatter<7>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
-        case 8: launch_scatter<8>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
-        case 9: launch_scatter<9>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
-        case 10: launch_scatter<10>(coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 2: launch_scatter<2>(morton_bits > 0, coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 3: launch_scatter<3>(morton_bits > 0, coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 4: launch_scatter<4>(morton_bits > 0, coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 5: launch_scatter<5>(morton_bits > 0, coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 6: launch_scatter<6>(morton_bits > 0, coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 7: launch_scatter<7>(morton_bits > 0, coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 8: launch_scatter<8>(morton_bits > 0, coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 9: launch_scatter<9>(morton_bits > 0, coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
+        case 10: launch_scatter<10>(morton_bits > 0, coords, n, bin_idx, rank, bounds, perm, soa, soa_stride, stream); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

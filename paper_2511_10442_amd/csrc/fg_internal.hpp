@@ -7,6 +7,8 @@
 namespace fg {
 
 constexpr int kGeomStride = 4;   // floats per (segment, binning dim): lo, inv_w, w, slack
+constexpr int kKeyStride = 16;   // words between two bounding-box keys: one 64-byte line each, so that the
+                                 // atomics on different keys do not queue up behind one another in one L2 line
 
 // Everything the query stage needs; plain device pointers.
 struct QueryArgs {
@@ -37,15 +39,19 @@ hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_
                           uint32_t* bbox_keys, float* geom, int32_t* bin_idx, int32_t* rank,
                           int32_t* perm, float* soa, int64_t soa_stride, int32_t* bounds,
                           int32_t* scan_partials,
-                          int32_t morton_bits /* 0: row-major bins; b > 0: n_bins = 2^b, bit-interleaved bin order */,
+                          int32_t morton_bits /* 0: row-major bins, bin-ordered SoA coordinates written to soa;
+                                                 b > 0 (the backward's row order): n_bins = 2^b, bit-interleaved bin order,
+                                                 only perm is written, plus for d = 3 a copy of coords in the original
+                                                 order padded to float4 in place of the SoA */,
                           hipStream_t stream);
 
 // d = 2..10, d_bin = 2..min(d,5)
 hipError_t launch_query(const QueryArgs& a, int32_t d, int32_t d_bin, hipStream_t stream);
 
-// perm != nullptr: rows are taken in bin order and combined in LDS; nullptr: plain atomic scatter
-hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, const int32_t* perm,
-                           int32_t n, int32_t d, int32_t k, float* grad_coords, hipStream_t stream);
+// perm != nullptr: rows are taken in bin order and combined in LDS; nullptr: plain atomic scatter.
+// coords4 (d = 3 with perm only, else nullptr): coords padded to four floats per row.
+hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, const float* coords4,
+                           const int32_t* perm, int32_t n, int32_t d, int32_t k, float* grad_coords, hipStream_t stream);
 
 hipError_t launch_oc_helper(const int32_t* asso_idx, const int32_t* unique_idx, const int32_t* unique_rs_asso,
                             const int32_t* rs, int32_t n_vert, int32_t n_unique, int32_t n_splits, int32_t n_maxuq,
