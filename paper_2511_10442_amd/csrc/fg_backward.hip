@@ -52,37 +52,95 @@ k_backward(const float* __restrict__ grad_d2, const int32_t* __restrict__ idx, c
     }
 }
 
+// lanes 16r .. 16r+15 of a wave: afterwards lane 16r+15 holds their sum
+__device__ __forceinline__ float row16_sum_to_last(float v)
+{
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x111, 0xf, 0xf, false));   // row_shr:1
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x112, 0xf, 0xf, false));   // row_shr:2
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x114, 0xf, 0xf, false));   // row_shr:4
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x118, 0xf, 0xf, false));   // row_shr:8
+    return v;
+}
+
 // ---- tiled variant: rows taken in bin order, neighbour-side contributions combined in LDS ----
 //
 // Device-scope float atomics are the bottleneck of the plain kernel (every one costs the same,
 // however local its address).  Rows that are adjacent in bin order are adjacent in space and
-// share most of their neighbours, so a block that takes kBwdRows consecutive bin-ordered rows
+// share most of their neighbours, so a block that takes a tile of consecutive bin-ordered rows
 // first adds all its contributions into an open-addressing hash table in LDS keyed by the
-// destination row (LDS float atomics), and only then issues one global atomic per distinct
-// destination and dimension.  Entries that find no slot within kBwdProbes probes go straight
-// to global memory, so the table size bounds nothing but speed.
+// destination row, and only then issues one global atomic per distinct destination and dimension.
+// The table accumulates in double precision: measured on gfx950 the LDS atomic add on doubles runs
+// about nine times faster than the one on floats (which handles about one lane every three cycles
+// per CU), and the sums come out more accurate as well.  Entries that find no slot within kBwdProbes
+// probes go straight to global memory, so the table size bounds nothing but speed.
+// Sizes, all measured on the 1M-point d = 3 K = 32 workload: 1024 threads per block and two blocks per CU (the
+// kernel waits on chains of dependent loads, row -> index -> coordinates, and on LDS round trips, so it wants
+// every wave slot filled: 256-thread blocks with the same table were 35 % slower); four table slots per row
+// (a tile's rows reach about two distinct destinations each).
 constexpr int kBwdProbes = 12;
-template <int D> constexpr int bwd_slots() { return D <= 4 ? 2048 : 1024; }
-template <int D> constexpr int bwd_rows() { return D <= 4 ? 256 : 128; }
+#ifndef FG_BWD_BATCH
+#define FG_BWD_BATCH 4
+#endif
+constexpr int kBwdBatch = FG_BWD_BATCH;   // (row, piece) pairs in flight per lane
+#ifndef FG_BWD_THREADS
+#define FG_BWD_THREADS 1024
+#endif
+template <int D> constexpr int bwd_block() { return FG_BWD_THREADS; }
+#ifndef FG_BWD_LDS_KB
+#define FG_BWD_LDS_KB 56
+#endif
+constexpr int pow2_floor(int v) { int p = 1; while (2 * p <= v) p *= 2; return p; }
+// table slots: the largest power of two whose keys (4 bytes) and D double sums fit the LDS budget of a block
+template <int D> constexpr int bwd_slots() { return pow2_floor(FG_BWD_LDS_KB * 1024 / (4 + 8 * D)); }
+#ifndef FG_BWD_ROWS_DIV
+#define FG_BWD_ROWS_DIV 4
+#endif
+template <int D> constexpr int bwd_rows() { return bwd_slots<D>() / FG_BWD_ROWS_DIV; }
+constexpr int ilog2(int v) { int b = 0; while ((1 << b) < v) ++b; return b; }
 
+// Adds kBwdBatch entries of one lane to the table (key u[e], D values each; u[e] < 0: nothing to add).
+// Open addressing with linear probing; the compare-and-swaps of one probe round are issued back to back
+// so that their round trips through the LDS overlap: those round trips, not the adds, are what the
+// table costs.
 template <int D>
-__device__ __forceinline__ void bwd_insert(int32_t* keys, float* vals, int32_t u, const float (&t)[D],
-                                           float* __restrict__ grad_coords)
+__device__ __forceinline__ void bwd_insert_batch(int32_t* keys, double* vals, const int32_t (&u)[kBwdBatch],
+                                                 const float (&t)[kBwdBatch][D], float* __restrict__ grad_coords)
 {
     constexpr int SLOTS = bwd_slots<D>();
-    uint32_t h = ((uint32_t)u * 2654435761u) >> (32 - (SLOTS == 2048 ? 11 : 10));
-#pragma unroll 1
-    for (int probe = 0; probe < kBwdProbes; ++probe) {
-        const int32_t prev = atomicCAS(&keys[h], -1, u);
-        if (prev == -1 || prev == u) {
+    uint32_t h[kBwdBatch];
+    bool open[kBwdBatch];
+    bool any_open = false;
 #pragma unroll
-            for (int c = 0; c < D; ++c) atomicAdd(&vals[c * SLOTS + h], t[c]);
-            return;
+    for (int e = 0; e < kBwdBatch; ++e) {
+        h[e] = ((uint32_t)u[e] * 2654435761u) >> (32 - ilog2(SLOTS));
+        open[e] = u[e] >= 0;
+        any_open = any_open || open[e];
+    }
+#pragma unroll 1
+    for (int probe = 0; probe < kBwdProbes && any_open; ++probe) {
+        int32_t prev[kBwdBatch];
+#pragma unroll
+        for (int e = 0; e < kBwdBatch; ++e) prev[e] = open[e] ? atomicCAS(&keys[h[e]], -1, u[e]) : 0;
+        any_open = false;
+#pragma unroll
+        for (int e = 0; e < kBwdBatch; ++e) {
+            if (!open[e]) continue;
+            if (prev[e] == -1 || prev[e] == u[e]) {
+#pragma unroll
+                for (int c = 0; c < D; ++c) atomicAdd(&vals[c * SLOTS + h[e]], (double)t[e][c]);
+                open[e] = false;
+            } else {
+                h[e] = (h[e] + 1) & (SLOTS - 1);
+                any_open = true;
+            }
         }
-        h = (h + 1) & (SLOTS - 1);
     }
 #pragma unroll
-    for (int c = 0; c < D; ++c) atomicAdd(&grad_coords[(int64_t)u * D + c], t[c]);
+    for (int e = 0; e < kBwdBatch; ++e) {
+        if (!open[e]) continue;
+#pragma unroll
+        for (int c = 0; c < D; ++c) atomicAdd(&grad_coords[(int64_t)u[e] * D + c], t[e][c]);
+    }
 }
 
 // One point's coordinates with as few load instructions as its row allows: the gathers of the
@@ -115,7 +173,7 @@ __device__ __forceinline__ void load_point(const float* __restrict__ coords, con
 }
 
 template <int D, bool VEC>
-__global__ void __launch_bounds__(kBwdBlock)
+__global__ void __launch_bounds__(bwd_block<D>())
 k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ idx, const float* __restrict__ coords,
                  const float4* __restrict__ coords4, const int32_t* __restrict__ perm, int32_t n, int32_t k,
                  float* __restrict__ grad_coords)
@@ -123,52 +181,69 @@ k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ 
     constexpr int SLOTS = bwd_slots<D>();
     constexpr int ROWS = bwd_rows<D>();
     __shared__ int32_t keys[SLOTS];
-    __shared__ float vals[D * SLOTS];
-    for (int i = threadIdx.x; i < SLOTS; i += kBwdBlock) keys[i] = -1;
-    for (int i = threadIdx.x; i < D * SLOTS; i += kBwdBlock) vals[i] = 0.0f;
+    __shared__ double vals[D * SLOTS];
+    for (int i = threadIdx.x; i < SLOTS; i += bwd_block<D>()) keys[i] = -1;
+    for (int i = threadIdx.x; i < D * SLOTS; i += bwd_block<D>()) vals[i] = 0.0;
     __syncthreads();
 
+    // A group of 16 lanes owns rows tile0 + sub, tile0 + sub + G, ... (G groups per block); lane l of the
+    // group takes entries j = l, l + 16, ... of each.  The (row, 16-entry piece) pairs of a group are walked
+    // kBwdBatch at a time with all loads of a batch issued before any of its LDS work: the chain row ->
+    // index -> neighbour coordinates is three dependent trips to memory, and one chain at a time left the
+    // kernel waiting on them.
+    constexpr int G = bwd_block<D>() / kLanesPerRow;
+    constexpr int ROWS_PER_GROUP = ROWS / G;
     const int l = threadIdx.x % kLanesPerRow;
     const int sub = threadIdx.x / kLanesPerRow;
     const int64_t tile0 = (int64_t)blockIdx.x * ROWS;
-    for (int r0 = 0; r0 < ROWS; r0 += kBwdBlock / kLanesPerRow) {
-        const int64_t pos = tile0 + r0 + sub;
-        const bool live = pos < n;                   // whole 16-lane groups are live or dead together
-        const int32_t v = live ? perm[pos] : 0;
-        float xv[D], acc[D];
-        load_point<D, VEC>(coords, coords4, v, xv);     // dead groups read row 0: harmless
+    const int32_t pieces = (k + kLanesPerRow - 1) / kLanesPerRow;
+    const int32_t n_it = ROWS_PER_GROUP * pieces;
+    for (int32_t it0 = 0; it0 < n_it; it0 += kBwdBatch) {
+        int32_t v[kBwdBatch], u[kBwdBatch];
+        float g2[kBwdBatch];
 #pragma unroll
-        for (int c = 0; c < D; ++c) acc[c] = 0.0f;
-        if (live) {
-            for (int32_t j = l; j < k; j += kLanesPerRow) {
-                const int32_t u = idx[(int64_t)v * k + j];
-                if (u < 0 || u >= n || u == v) continue;   // padding / out of range: ignored; self contributes exactly 0
-                const float g2 = 2.0f * grad_d2[(int64_t)v * k + j];
-                float t[D], xu[D];
-                load_point<D, VEC>(coords, coords4, u, xu);
-#pragma unroll
-                for (int c = 0; c < D; ++c) {
-                    const float tc = g2 * (xv[c] - xu[c]);
-                    acc[c] += tc;
-                    t[c] = -tc;
-                }
-                bwd_insert<D>(keys, vals, u, t, grad_coords);
-            }
+        for (int e = 0; e < kBwdBatch; ++e) {
+            const int32_t it = it0 + e;
+            const int32_t ri = it / pieces;
+            const int32_t j = (it - ri * pieces) * kLanesPerRow + l;
+            const int64_t pos = tile0 + (int64_t)ri * G + sub;
+            const bool live = it < n_it && pos < n;      // whole 16-lane groups are live or dead together
+            v[e] = live ? perm[pos] : -1;
+            const bool has = live && j < k;
+            u[e] = has ? idx[(int64_t)v[e] * k + j] : -1;
+            g2[e] = has ? 2.0f * grad_d2[(int64_t)v[e] * k + j] : 0.0f;
+            if (u[e] >= n || u[e] == v[e]) u[e] = -1;    // out of range: ignored; self contributes exactly 0
         }
+        float xv[kBwdBatch][D], xu[kBwdBatch][D];
 #pragma unroll
-        for (int c = 0; c < D; ++c) {
-            float s = acc[c];
-            for (int o = kLanesPerRow / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
-            acc[c] = s;
+        for (int e = 0; e < kBwdBatch; ++e) {
+            load_point<D, VEC>(coords, coords4, v[e] < 0 ? 0 : v[e], xv[e]);
+            load_point<D, VEC>(coords, coords4, u[e] < 0 ? 0 : u[e], xu[e]);
         }
-        if (live && l == 0) bwd_insert<D>(keys, vals, v, acc, grad_coords);
+        // neighbour side of the whole batch, then the rows' own side: each piece summed over its 16 lanes (one
+        // DPP row: four shifted adds leave the total in the row's last lane, no trip through the LDS crossbar)
+        // and added by that lane
+        float t[kBwdBatch][D];
+        int32_t own[kBwdBatch];
+#pragma unroll
+        for (int e = 0; e < kBwdBatch; ++e)
+#pragma unroll
+            for (int c = 0; c < D; ++c) t[e][c] = u[e] >= 0 ? g2[e] * (xu[e][c] - xv[e][c]) : 0.0f;
+        bwd_insert_batch<D>(keys, vals, u, t, grad_coords);
+#pragma unroll
+        for (int e = 0; e < kBwdBatch; ++e) {
+#pragma unroll
+            for (int c = 0; c < D; ++c) t[e][c] = row16_sum_to_last(-t[e][c]);
+            own[e] = l == kLanesPerRow - 1 ? v[e] : -1;
+        }
+        bwd_insert_batch<D>(keys, vals, own, t, grad_coords);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < SLOTS; i += kBwdBlock) {
+    for (int i = threadIdx.x; i < SLOTS; i += bwd_block<D>()) {
         const int32_t u = keys[i];
         if (u >= 0) {
 #pragma unroll
-            for (int c = 0; c < D; ++c) atomicAdd(&grad_coords[(int64_t)u * D + c], vals[c * SLOTS + i]);
+            for (int c = 0; c < D; ++c) atomicAdd(&grad_coords[(int64_t)u * D + c], (float)vals[c * SLOTS + i]);
         }
     }
 }
@@ -179,10 +254,10 @@ static void launch_bwd_tiled(const float* grad_d2, const int32_t* idx, const flo
 {
     unsigned grid = (unsigned)((n + bwd_rows<D>() - 1) / bwd_rows<D>());
     if (((uintptr_t)coords % 16) == 0)
-        hipLaunchKernelGGL((k_backward_tiled<D, true>), dim3(grid), dim3(kBwdBlock), 0, stream, grad_d2, idx, coords,
+        hipLaunchKernelGGL((k_backward_tiled<D, true>), dim3(grid), dim3(bwd_block<D>()), 0, stream, grad_d2, idx, coords,
                            coords4, perm, n, k, grad_coords);
     else
-        hipLaunchKernelGGL((k_backward_tiled<D, false>), dim3(grid), dim3(kBwdBlock), 0, stream, grad_d2, idx, coords,
+        hipLaunchKernelGGL((k_backward_tiled<D, false>), dim3(grid), dim3(bwd_block<D>()), 0, stream, grad_d2, idx, coords,
                            coords4, perm, n, k, grad_coords);
 }
 
