@@ -31,6 +31,9 @@ template <int KC> constexpr int tile_waves() { return KC <= 16 ? 4 : (KC == 32 ?
 constexpr int kPend = 16;   // pending keys per lane between two merges
 struct Ranges { int32_t a1, b1, a2, b2; };
 
+// row pitch of the output transposition in LDS: 65 words, so that the lanes writing one output row (consecutive
+// slots of one query) read 65 words apart and spread over the banks instead of all landing in one
+constexpr int kDumpStride = kQueryBlock + 1;
 constexpr int kUnroll = 4;  // candidates per lane per pass of the scan loop (independent LDS reads in flight)
 
 // staged point = its D coordinates followed by its original index, padded to whole float4s
@@ -306,7 +309,7 @@ k_query_tile_sorted(QueryArgs a)
             const bool real = best[i] < kEmptyKey;
             const uint32_t word = pass == 0 ? (real ? (uint32_t)best[i] : 0xffffffffu)      // index or -1
                                             : (real ? (uint32_t)(best[i] >> 32) : 0u);       // distance bits or 0.0f
-            dump[i * kQueryBlock + lane] = word;
+            dump[i * kDumpStride + lane] = word;
         }
         __syncthreads();
         for (int32_t r0 = 0; r0 < kQueryBlock; r0 += per_iter) {
@@ -318,7 +321,7 @@ k_query_tile_sorted(QueryArgs a)
             for (int32_t j = j0; j < k; j += kQueryBlock) {
                 uint32_t word = pass == 0 ? (enc >= 0 ? (uint32_t)row : 0xffffffffu) : 0u;   // slot 0: the row itself at distance 0
                 if (pass == 1 && ((mask >> ql) & 1)) word = resume_word;                     // handed over: where to resume
-                if (j > 0) word = dump[(KC - cap + j - 1) * kQueryBlock + ql];
+                if (j > 0) word = dump[(KC - cap + j - 1) * kDumpStride + ql];
                 if (pass == 0) a.out_idx[(int64_t)row * k + j] = (int32_t)word;
                 else a.out_d2[(int64_t)row * k + j] = __uint_as_float(word);
             }
@@ -344,7 +347,7 @@ template <int KC, int D>
 constexpr size_t tile_sorted_lds_bytes()
 {
     const size_t scan = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (kStageChunk + kUnroll);
-    const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kQueryBlock * 4;
+    const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kDumpStride * 4;
     return scan > out ? scan : out;
 }
 
