@@ -93,6 +93,8 @@ typedef struct {
                                   wavefront goes on to the next shell only while more than this many of its 64
                                   queries are unfinished (and its lanes have been evenly loaded so far); the
                                   rest go to the list kernel.  Result-neutral. */
+    int32_t* tile_order;       /* [2*ceil(n/64) + 128]  scratch of the query stage: the order in which the tile
+                                  kernel takes its tiles of 64 bin-ordered queries (most work first) */
 } fg_binning;
 
 /* Spatial partition + counting sort (Section 3: "points are sorted by bin assignments and

@@ -40,7 +40,7 @@ class _Binning(ctypes.Structure):
                 ("cells_per_segment", ctypes.c_int64), ("n_bins", ctypes.c_int32),
                 ("d_bin", ctypes.c_int32), ("work_list", ctypes.c_void_p),
                 ("work_count", ctypes.c_void_p), ("dir", ctypes.c_void_p), ("query_algo", ctypes.c_int32),
-                ("defer_lanes", ctypes.c_int32)]
+                ("defer_lanes", ctypes.c_int32), ("tile_order", ctypes.c_void_p)]
 
 
 _lib = None

@@ -56,7 +56,7 @@ constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 struct Layout {
-    size_t keys, geom, bin_idx, rank, perm, soa, bounds, partials, work_list, work_count, total;
+    size_t keys, geom, bin_idx, rank, perm, soa, bounds, partials, work_list, work_count, tile_order, total;
     int64_t soa_stride, total_bins, cells_per_segment;
 };
 
@@ -81,6 +81,7 @@ Layout make_layout(int64_t n, int32_t d, int32_t n_segments, int32_t n_bins, int
     L.partials = off; off = align_up(off + sizeof(int32_t) * (size_t)((L.total_bins + 1 + kScanChunkHost - 1) / kScanChunkHost));
     L.work_list = off; off = align_up(off + sizeof(int32_t) * (size_t)n);
     L.work_count = off; off = align_up(off + sizeof(int32_t));
+    L.tile_order = off; off = align_up(off + sizeof(int32_t) * (size_t)(2 * ((n + 63) / 64) + 128));
     L.total = off;
     return L;
 }
@@ -224,6 +225,7 @@ static fg_status bin_points_impl(const float* coords, const int32_t* row_splits,
     view->d_bin = d_bin;
     view->work_list = (int32_t*)(ws + L.work_list);
     view->work_count = (int32_t*)(ws + L.work_count);
+    view->tile_order = (int32_t*)(ws + L.tile_order);
     view->dir = nullptr;
     view->query_algo = 0;
     view->defer_lanes = kDefaultDeferLanes;
@@ -269,7 +271,7 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
     a.row_splits = row_splits; a.dir = view->dir; a.out_idx = out_idx; a.out_d2 = out_d2; a.out_cand = out_candidates;
     a.soa_stride = view->soa_stride; a.n = (int32_t)n; a.n_segments = n_segments; a.k = k;
     a.n_bins = view->n_bins; a.cells_per_segment = (int32_t)view->cells_per_segment;
-    a.work_list = view->work_list; a.work_count = view->work_count; a.algo = view->query_algo == 1 ? 1 : 0;
+    a.work_list = view->work_list; a.work_count = view->work_count; a.bin_idx = view->bin_idx; a.tile_order = view->tile_order; a.algo = view->query_algo == 1 ? 1 : 0;
     a.defer_lanes = view->defer_lanes < 0 ? 0 : (view->defer_lanes > 64 ? 64 : view->defer_lanes);
     hipError_t e = launch_query(a, d, view->d_bin, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;

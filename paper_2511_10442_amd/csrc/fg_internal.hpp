@@ -23,6 +23,8 @@ struct QueryArgs {
     int32_t* out_cand;         // [n] or nullptr
     int32_t* work_list;        // [n] sorted positions of queries deferred by the tile kernel
     int32_t* work_count;       // [1]
+    const int32_t* bin_idx;    // [n] flat bin of each point, original row order
+    int32_t* tile_order;       // [2*ceil(n/64) + 128]: tile order, tile classes, class histogram, class cursors
     int64_t soa_stride;
     int32_t n;
     int32_t n_segments;

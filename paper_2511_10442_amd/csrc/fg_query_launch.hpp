@@ -6,7 +6,166 @@
 
 namespace fg {
 
-static __global__ void k_reset_counter(int32_t* c) { if (threadIdx.x == 0) *c = 0; }
+// ---- tile order: heaviest tiles first --------------------------------------------------------
+// Tiles differ in cost by more than an order of magnitude (a tile inside a dense cluster scans thousands of
+// candidates per query) and the hardware hands out workgroups in index order, so a heavy tile that starts late
+// sets the kernel's end: measured on the 1M-point clustered workload the tile kernel took 1.2 ms for 0.73 ms of
+// evenly spread work, the last third of it with most of the chip idle.  The tiles are therefore ranked by an
+// estimate of their work, in 64 classes of half a power of two, heaviest class first.
+// tile_order: [0, T) the order, [T, 2T) class of each tile, [2T, 2T+64) class histogram, [2T+64, 2T+128) cursors.
+constexpr int kTileClasses = 64;
+
+static __global__ void k_reset_query_scratch(int32_t* work_count, int32_t* tile_counters)
+{
+    if (threadIdx.x == 0) *work_count = 0;
+    if (tile_counters && threadIdx.x < 2 * kTileClasses) tile_counters[threadIdx.x] = 0;
+}
+
+__device__ __forceinline__ int32_t tile_class(int32_t work)
+{
+    if (work < 2) return work < 1 ? 0 : 1;
+    const int32_t lg = 31 - __clz(work);
+    const int32_t c = 2 * lg + ((work >> (lg - 1)) & 1);
+    return c < kTileClasses ? c : kTileClasses - 1;
+}
+
+constexpr int kTilesPerWave = 16;
+
+// Work estimate of a tile: what the first two shells cost it without any pruning, i.e. for every column of the
+// 3 x ... x 3 neighbourhood the longest candidate run any of its queries has there (the tile kernel scans a
+// column for as long as its busiest lane needs), summed over the columns.  Taken over 8 of the tile's 64 queries
+// (every ninth: consecutive queries mostly share their bins), 8 tiles per wavefront at a time: with all 64 the
+// gathers of the bin boundaries made this kernel cost 73 us per million points.
+constexpr int kTileSamples = 8;
+
+// maximum / sum over each aligned group of 8 lanes, returned in all 8 (DPP: swap inside pairs, swap pairs, mirror the half row)
+__device__ __forceinline__ int32_t oct_max_i32(int32_t v)
+{
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0xb1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x4e, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xf, 0xf, false));   // row_half_mirror
+    return v;
+}
+__device__ __forceinline__ int32_t oct_sum_i32(int32_t v)
+{
+    v += __builtin_amdgcn_update_dpp(v, v, 0xb1, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(v, v, 0x4e, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(v, v, 0x141, 0xf, 0xf, false);
+    return v;
+}
+
+template <int DB>
+static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n_tiles)
+{
+    __shared__ int32_t hist[kTileClasses];
+    if (threadIdx.x < kTileClasses) hist[threadIdx.x] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int sample = lane & (kTileSamples - 1);
+    const int32_t wave_t0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * kTilesPerWave;
+    int32_t ncols = 1;
+#pragma unroll
+    for (int c = 0; c < DB - 1; ++c) ncols *= 3;
+    for (int32_t tb = wave_t0; tb < wave_t0 + kTilesPerWave; tb += kQueryBlock / kTileSamples) {
+        const int32_t t = tb + (lane >> 3);
+        const int32_t p = t * kQueryBlock + sample * 9;            // queries 0, 9, ..., 63 of the tile
+        const bool live = t < n_tiles && p < a.n;
+        int32_t cc[DB], seg_cell0 = 0;
+        {
+            const int32_t b = live ? a.bin_idx[a.perm[p]] : 0;
+            int32_t r = b % a.cells_per_segment;
+            seg_cell0 = b - r;
+#pragma unroll
+            for (int c = DB - 1; c >= 0; --c) { cc[c] = r % a.n_bins; r /= a.n_bins; }
+        }
+        int32_t work = 0, around = 0;
+        for (int32_t col = 0; col < ncols; ++col) {
+            int32_t rem = col, flat = 0;
+            bool ok = live;
+#pragma unroll
+            for (int c = 0; c < DB - 1; ++c) {     // digit c of col -> offset -1, 0, +1 in dimension c
+                const int32_t j = cc[c] + rem % 3 - 1;
+                rem /= 3;
+                ok = ok && j >= 0 && j < a.n_bins;
+                flat = flat * a.n_bins + j;
+            }
+            int32_t len = 0;
+            if (ok) {
+                const int32_t cz = cc[DB - 1];
+                const int32_t za = cz > 0 ? cz - 1 : 0, zb = cz < a.n_bins - 1 ? cz + 1 : a.n_bins - 1;
+                const int32_t row = seg_cell0 + flat * a.n_bins;
+                len = a.bounds[row + zb + 1] - a.bounds[row + za];
+            }
+            around += len;
+            work += oct_max_i32(len) >> 2;         // in passes of four; keeps the sum small
+        }
+        // A query with few points around it will not be certified after shell 1 (the k-th neighbour of a query at
+        // the centre of its bin lies inside the inscribed ball of the 3-bin cube, about a sixth of its volume, only
+        // if the cube holds some 6 K points); where more such queries than the tile kernel hands over are expected,
+        // the tile will go on to shell 2: 5 x ... x 5 columns of 5-bin runs.
+        const bool lonely = live && around < 4 * (a.k - 1);
+        const bool goes_on = oct_sum_i32(lonely ? 1 : 0) * (kQueryBlock / kTileSamples) > a.defer_lanes;
+        if (__any(goes_on)) {
+            int32_t ncols2 = 1;
+#pragma unroll
+            for (int c = 0; c < DB - 1; ++c) ncols2 *= 5;
+            for (int32_t col = 0; col < ncols2; ++col) {
+                int32_t rem = col, flat = 0;
+                bool ok = lonely && goes_on;
+#pragma unroll
+                for (int c = 0; c < DB - 1; ++c) {
+                    const int32_t j = cc[c] + rem % 5 - 2;
+                    rem /= 5;
+                    ok = ok && j >= 0 && j < a.n_bins;
+                    flat = flat * a.n_bins + j;
+                }
+                int32_t len = 0;
+                if (ok) {
+                    const int32_t cz = cc[DB - 1];
+                    const int32_t za = cz > 1 ? cz - 2 : 0, zb = cz < a.n_bins - 2 ? cz + 2 : a.n_bins - 1;
+                    const int32_t row = seg_cell0 + flat * a.n_bins;
+                    len = a.bounds[row + zb + 1] - a.bounds[row + za];
+                }
+                work += oct_max_i32(len) >> 2;
+            }
+        }
+        if (sample == 0 && t < n_tiles) {
+            const int32_t cls = tile_class(work);
+            a.tile_order[n_tiles + t] = cls;
+            atomicAdd(&hist[cls], 1);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < kTileClasses && hist[threadIdx.x] > 0)
+        atomicAdd(&a.tile_order[2 * n_tiles + threadIdx.x], hist[threadIdx.x]);
+}
+
+// Position of every tile: classes in descending order; inside a class roughly the bin order (blocks of 256
+// consecutive tiles reserve their places with one atomic per class, and a block's tiles keep the order in which
+// its waves arrive), so that tiles running at the same time still share their neighbourhoods in the L2 cache.
+static __global__ void __launch_bounds__(256) k_tile_rank(int32_t* __restrict__ order, int32_t n_tiles)
+{
+    __shared__ int32_t local[kTileClasses];   // this block's tiles per class, then the block's first position in the class
+    __shared__ int32_t first[kTileClasses];   // position of the class's first tile: all heavier classes before it
+    if (threadIdx.x < kTileClasses) {
+        local[threadIdx.x] = 0;
+        int32_t s = 0;
+        for (int c = threadIdx.x + 1; c < kTileClasses; ++c) s += order[2 * n_tiles + c];
+        first[threadIdx.x] = s;
+    }
+    __syncthreads();
+    const int32_t t = blockIdx.x * 256 + threadIdx.x;
+    int32_t cls = 0, mine = 0;
+    if (t < n_tiles) {
+        cls = order[n_tiles + t];
+        mine = atomicAdd(&local[cls], 1);
+    }
+    __syncthreads();
+    if (threadIdx.x < kTileClasses && local[threadIdx.x] > 0)
+        local[threadIdx.x] = atomicAdd(&order[2 * n_tiles + kTileClasses + threadIdx.x], local[threadIdx.x]);
+    __syncthreads();
+    if (t < n_tiles) order[first[cls] + local[cls] + mine] = t;
+}
 
 template <typename K>
 static void allow_lds(K kernel, size_t bytes)
@@ -15,8 +174,9 @@ static void allow_lds(K kernel, size_t bytes)
 }
 
 template <int D, int DB, bool COUNT>
-static hipError_t launch_query_impl(const QueryArgs& a, hipStream_t stream)
+static hipError_t launch_query_impl(const QueryArgs& a_in, hipStream_t stream)
 {
+    QueryArgs a = a_in;
     const int grid = (a.n + kQueryBlock - 1) / kQueryBlock;
     const size_t heap_bytes = (size_t)(a.k > 1 ? a.k - 1 : 1) * kQueryBlock * sizeof(uint64_t);
     if (a.algo == 1) {
@@ -25,7 +185,15 @@ static hipError_t launch_query_impl(const QueryArgs& a, hipStream_t stream)
         return hipGetLastError();
     }
     allow_lds(k_query_list<D, DB, COUNT>, heap_bytes);
-    hipLaunchKernelGGL(k_reset_counter, dim3(1), dim3(64), 0, stream, a.work_count);
+    const bool ordered = a.tile_order && a.bin_idx && grid > 1024;    // a few waves per SIMD: nothing to reorder
+    hipLaunchKernelGGL(k_reset_query_scratch, dim3(1), dim3(2 * kTileClasses), 0, stream, a.work_count,
+                       ordered ? a.tile_order + 2 * grid : nullptr);
+    if (ordered) {
+        hipLaunchKernelGGL(k_tile_work<DB>, dim3((grid + 4 * kTilesPerWave - 1) / (4 * kTilesPerWave)), dim3(256), 0, stream, a, grid);
+        hipLaunchKernelGGL(k_tile_rank, dim3((grid + 255) / 256), dim3(256), 0, stream, a.tile_order, grid);
+    } else {
+        a.tile_order = nullptr;
+    }
     const int32_t cap = a.k - 1;
     if (cap <= 16) {
         const size_t lds = tile_sorted_lds_bytes<16, D>();

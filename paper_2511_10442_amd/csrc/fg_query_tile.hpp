@@ -55,7 +55,8 @@ k_query_tile_sorted(QueryArgs a)
     float4* stage = reinterpret_cast<float4*>(lds64 + kPend * kQueryBlock);   // [kStageChunk][NV]
 
     const int32_t cap = a.k - 1;          // 0 <= cap <= KC
-    const int32_t p = blockIdx.x * kQueryBlock + lane;
+    const int32_t tile = a.tile_order ? a.tile_order[blockIdx.x] : (int32_t)blockIdx.x;   // heaviest tiles first
+    const int32_t p = tile * kQueryBlock + lane;
     const bool valid = p < a.n;
     LaneGeom<D, DB> s;
     s.init_geom(a, valid ? p : a.n - 1);  // dead lanes shadow the last point, never scan or write
@@ -64,6 +65,7 @@ k_query_tile_sorted(QueryArgs a)
     bool active = valid && cap > 0 && asks;
 
 #ifdef FG_TILE_PROF
+    const unsigned long long w_start = wall_clock64();
     long long t_all = clock64(), t_setup = 0, t_stage = 0, t_scan = 0, t_absorb = 0, t_out = 0, tt;
     int n_cols = 0, n_chunks = 0, n_iter = 0, n_absorb = 0, last_R = 0, n_acc = 0;
 #define PROF_T0 tt = clock64();
@@ -331,14 +333,18 @@ k_query_tile_sorted(QueryArgs a)
     PROF_ADD(t_out)
     const int32_t pu_max = wave_max_i32(useful), pu_sum = wave_sum_i32(useful);
     const int32_t pa_max = wave_max_i32(n_acc), pa_sum = wave_sum_i32(n_acc);
-    if (COUNT && lane == 0 && (blockIdx.x + 1) * 64 <= a.n) {
+    if (COUNT && lane == 0 && (tile + 1) * 64 <= a.n) {
         __syncthreads();
-        int32_t* pr = a.out_cand + blockIdx.x * 64;   // debug build only: the tile's 64 count slots carry the profile
+        int32_t* pr = a.out_cand + tile * 64;   // debug build only: the tile's 64 count slots carry the profile
         pr[0] = (int32_t)((clock64() - t_all) >> 4); pr[1] = (int32_t)(t_setup >> 4); pr[2] = (int32_t)(t_stage >> 4);
         pr[3] = (int32_t)(t_scan >> 4); pr[4] = (int32_t)(t_absorb >> 4); pr[5] = last_R; pr[6] = n_cols;
         pr[7] = n_chunks; pr[8] = n_iter; pr[9] = n_absorb; pr[10] = (int32_t)(t_out >> 4);
         pr[11] = __popcll(mask);
         pr[12] = pu_max; pr[13] = pu_sum / 64; pr[14] = pa_max; pr[15] = pa_sum / 64;
+        pr[16] = (int32_t)(uint32_t)w_start; pr[17] = (int32_t)(uint32_t)wall_clock64();
+        pr[18] = (int32_t)__builtin_amdgcn_s_getreg(63492);    // HW_ID
+        pr[19] = (int32_t)__builtin_amdgcn_s_getreg(63508);    // XCC_ID
+        pr[20] = (int32_t)blockIdx.x;
     }
 #endif
 }
