@@ -127,11 +127,19 @@ def main() -> int:
     total_bins = binning.n_segments * binning.cells_per_segment
     algo_bytes = n * (k * 8 + d * 4 + 4) + (total_bins + 1) * 4
     achieved = algo_bytes / (ms_query * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "query stage = k_query_tile_sorted + k_query_list_wave (two launches)",
+    roofline = {"bound": "hbm", "kernel": "query stage = k_query_tile_sorted (dominant) + k_query_list_wave + the tile-order kernels",
                 "achieved": round(achieved, 2), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
                 "traffic": _traffic_from_profiles("query_kernel_%s_traffic.txt" % w.name.split("_")[0]),
                 "algorithmic_bytes_per_launch": algo_bytes, "kernel_ms": round(ms_query, 4)}
+
+    # the same stage against what actually bounds it: one float32 operation per lane and clock (no FMA by the
+    # definition of the distance, packed float32 off): 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz
+    alu_peak = 256 * 4 * 16 * 2.4e9 / 1e12
+    alu_achieved = total_cand * (3 * d - 1) / (ms_query * 1e-3) / 1e12
+    roofline_alu = {"bound": "alu", "achieved": round(alu_achieved, 3), "peak": round(alu_peak, 1), "unit": "TFLOP/s",
+                    "frac": round(alu_achieved / alu_peak, 5),
+                    "note": "distance arithmetic only (3d-1 float32 operations per candidate); selection work not counted"}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -155,6 +163,7 @@ def main() -> int:
                    "n_bins": binning.n_bins, "d_bin": binning.d_bin,
                    "step": "fg_binned_select_knn" + (" + fg_knn_backward" if w.backward else "")},
         "roofline": roofline,
+        "roofline_alu": roofline_alu,
         "cpu_baseline": cpu,
         "stages": {"binning_ms": round(ms_bin, 4), "query_ms": round(ms_query, 4),
                    "backward_ms": None if ms_bwd is None else round(ms_bwd, 4),
