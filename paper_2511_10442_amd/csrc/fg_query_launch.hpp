@@ -215,7 +215,9 @@ static hipError_t launch_query_impl(const QueryArgs& a_in, hipStream_t stream)
         hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 128, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     }
     if (cap <= 64) {   // one query per wavefront
-        const int list_grid = a.n < 8192 ? a.n : 8192;
+        // four times the wave slots of the chip: the queries differ widely in cost, and with more, shorter
+        // workgroups the hardware dispatcher evens them out (cursors in memory cost more than they gained)
+        const int list_grid = a.n < 32768 ? a.n : 32768;
         hipLaunchKernelGGL((k_query_list_wave<D, DB, COUNT>), dim3(list_grid), dim3(kQueryBlock), 0, stream, a);
     } else {
         const int list_grid = grid < 4096 ? grid : 4096;
