@@ -50,7 +50,11 @@ k_query_tile_sorted(QueryArgs a)
     // pending keys: index words [kPend][64], then distance words [kPend][64]
     uint32_t* const pend_lds = reinterpret_cast<uint32_t*>(lds64) + lane;
     constexpr int kPendHalf = kPend * kQueryBlock;
-    uint32_t* pend_top = pend_lds;        // next free slot of this lane
+    // next free slot of this lane, kept as a plain LDS byte address so that an accepted candidate costs one
+    // two-word store and one add (a pointer relative to pend_lds cost a second add per candidate)
+    using lds_word = __attribute__((address_space(3))) uint32_t;
+    const uint32_t pend_base = (uint32_t)(uintptr_t)(lds_word*)pend_lds;
+    uint32_t pend_top = pend_base;
     constexpr int NV = stage_vecs<D>();
     float4* stage = reinterpret_cast<float4*>(lds64 + kPend * kQueryBlock);   // [kStageChunk][NV]
 
@@ -83,7 +87,7 @@ k_query_tile_sorted(QueryArgs a)
 
     auto absorb = [&]() {
         uint64_t pend[kPend];
-        const int32_t cnt = (int32_t)(pend_top - pend_lds) / kQueryBlock;
+        const int32_t cnt = (int32_t)((pend_top - pend_base) / (kQueryBlock * 4));
 #pragma unroll
         for (int i = 0; i < kPend; ++i) {
             const uint64_t v = ((uint64_t)pend_lds[kPendHalf + i * kQueryBlock] << 32) | pend_lds[i * kQueryBlock];
@@ -94,12 +98,12 @@ k_query_tile_sorted(QueryArgs a)
 #ifdef FG_TILE_PROF
         n_acc += cnt;
 #endif
-        pend_top = pend_lds;
+        pend_top = pend_base;
         s.tau = best[KC - 1];
     };
 
     int32_t R = 0;
-    const uint32_t* const pend_full = pend_lds + (kPend - kUnroll) * kQueryBlock;   // beyond this a pass may overflow
+    const uint32_t pend_full = pend_base + (kPend - kUnroll) * kQueryBlock * 4;   // beyond this a pass may overflow
     for (;; ++R) {   // ends at the latest at R = n_bins - 1, when every lane's cube covers its grid
         const int32_t side = 2 * R + 1;
         int32_t ncols = 1;
@@ -213,8 +217,9 @@ k_query_tile_sorted(QueryArgs a)
                 int32_t q = a1 > base ? a1 : base, e = b1 < top ? b1 : top;
                 int32_t q2 = a2 > base ? a2 : base, e2 = b2 < top ? b2 : top;
                 useful += (e > q ? e - q : 0) + (e2 > q2 ? e2 - q2 : 0);
+                const bool second_runs = __any(e2 > q2);      // only the centre column (and shell 0) has two runs per lane
                 for (;;) {
-                    if (q >= e && q2 < e2) { q = q2; e = e2; q2 = e2; }
+                    if (second_runs && q >= e && q2 < e2) { q = q2; e = e2; q2 = e2; }
                     const int32_t rem = e - q;
                     if (!__any(rem > 0)) break;
                     float w[kUnroll][NV * 4];
@@ -243,9 +248,11 @@ k_query_tile_sorted(QueryArgs a)
                         // on the index: the merge decides); NaN (poisoned) patterns lie above every bound
                         const uint32_t bits = __float_as_uint(d2);
                         if (live && bits <= tau_hi) {
-                            pend_top[0] = __float_as_uint(w[u][D]);
-                            pend_top[kPendHalf] = bits;
-                            pend_top += kQueryBlock;
+                            // index word and distance word kPend planes apart, then the slot pointer moves on:
+                            // written out because the compiler spends a third instruction on a register copy
+                            static_assert(kPendHalf * 4 == 16 * 256 && kQueryBlock * 4 == 0x100, "offsets below");
+                            asm volatile("ds_write2st64_b32 %0, %1, %2 offset1:16\n\tv_add_u32 %0, 0x100, %0"
+                                         : "+v"(pend_top) : "v"(__float_as_uint(w[u][D])), "v"(bits) : "memory");
                         }
                     }
                     q += kUnroll;
@@ -261,7 +268,7 @@ k_query_tile_sorted(QueryArgs a)
             }
         }
         PROF_T0
-        if (__any(pend_top != pend_lds)) absorb();
+        if (__any(pend_top != pend_base)) absorb();
         PROF_ADD(t_absorb)
         if (active && s.certified(R)) active = false;
         const int32_t n_active = __popcll(__ballot(active));
