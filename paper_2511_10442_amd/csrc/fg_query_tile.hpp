@@ -26,8 +26,15 @@ namespace fg {
 #ifndef FG_TILE_WAVES32
 #define FG_TILE_WAVES32 3
 #endif
-// waves per SIMD the register allocator aims at: the sorted list alone takes 2*KC registers
-template <int KC> constexpr int tile_waves() { return KC <= 16 ? 4 : (KC == 32 ? FG_TILE_WAVES32 : (KC <= 64 ? 2 : 1)); }
+// Waves per SIMD the register allocator aims at: the sorted list alone takes 2*KC registers.  Measured choices:
+// KC = 32 at three (two are 18 % slower, four spill into the scan loop and are slower too); KC = 48 at three for
+// d <= 3 (12 % faster than two although a few registers spill outside the loops; with d >= 4 a staged candidate
+// takes two more vector registers per unrolled slot and three waves lose 8 %); beyond 64 keys the list no longer
+// fits the 256 architectural registers of a wave and the kernel runs at one wave per SIMD.
+template <int KC, int D> constexpr int tile_waves()
+{
+    return KC <= 16 ? 4 : (KC == 32 ? FG_TILE_WAVES32 : (KC == 48 ? (D <= 3 ? 3 : 2) : (KC <= 64 ? 2 : 1)));
+}
 constexpr int kPend = 16;   // pending keys per lane between two merges
 struct Ranges { int32_t a1, b1, a2, b2; };
 
@@ -40,7 +47,7 @@ constexpr int kUnroll = 4;  // candidates per lane per pass of the scan loop (in
 template <int D> constexpr int stage_vecs() { return (D + 1 + 3) / 4; }
 
 template <int D, int DB, int KC, bool COUNT>
-__global__ void __launch_bounds__(kQueryBlock) __attribute__((amdgpu_waves_per_eu(tile_waves<KC>(), tile_waves<KC>())))
+__global__ void __launch_bounds__(kQueryBlock) __attribute__((amdgpu_waves_per_eu(tile_waves<KC, D>(), tile_waves<KC, D>())))
 k_query_tile_sorted(QueryArgs a)
 {
     // LDS: [pending kPend x 64 keys][stage (D+1) x kStageChunk words]; re-used at the end as
