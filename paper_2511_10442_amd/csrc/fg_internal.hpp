@@ -28,7 +28,9 @@ struct QueryArgs {
     int64_t soa_stride;
     int32_t n;
     int32_t n_segments;
-    int32_t k;
+    int32_t k;                 // slots per output row
+    int32_t slot0;             // tile + list kernels: neighbours already placed by an earlier pass (0 or 64); this pass keeps only keys above the one in row slot `slot0`
+    int32_t k_list;            // tile + list kernels: neighbours this pass finds (1..64, or 0 for K = 1); they go to row slots slot0+1 .. slot0+k_list
     int32_t n_bins;
     int32_t cells_per_segment;
     int32_t algo;              // 0: tile kernel + list kernel, 1: one lane per query for everything

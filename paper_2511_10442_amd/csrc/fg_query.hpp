@@ -1,7 +1,6 @@
 // Per-lane geometry shared by all query kernels, and the general shell-expanding walk with one
-// lane per query (any shell radius).  The walk is the cross-check path (query_algo = 1) and the
-// list pass for K-1 > 64; the fast path is the tile kernel plus the one-query-per-wavefront list
-// kernel.
+// lane per query (any shell radius).  The walk is the cross-check path (query_algo = 1); the fast path is
+// the tile kernel plus the one-query-per-wavefront list kernel.
 //
 // What it computes (paper Section 3, Algorithm 2): for every point, the K-1 nearest other
 // points of its row split, found by scanning the bins on the surface of the hypercube of
@@ -307,22 +306,6 @@ __device__ __forceinline__ int32_t wave_max_i32(int32_t v)
     v = max(v, __builtin_amdgcn_update_dpp(id, v, 0x142, 0xa, 0xf, false));
     v = max(v, __builtin_amdgcn_update_dpp(id, v, 0x143, 0xc, 0xf, false));
     return __builtin_amdgcn_readlane(v, 63);
-}
-
-// ---- list pass, one lane per query: the general shell walk over the deferred queries (used when K-1 > 64) ----
-template <int D, int DB, bool COUNT>
-__global__ void __launch_bounds__(kQueryBlock)
-k_query_list(QueryArgs a)
-{
-    extern __shared__ uint64_t lds64[];
-    const int32_t count = *a.work_count;
-    for (int32_t i = blockIdx.x * kQueryBlock + threadIdx.x; i < count; i += gridDim.x * kQueryBlock) {
-        const int32_t p = a.work_list[i];
-        ShellSearch<D, DB, COUNT> s;
-        init_lane(s, a, p, lds64 + threadIdx.x);
-        s.run();
-        write_row(s, a, p, true);
-    }
 }
 
 // all queries through the one-lane-per-query walk (no tiles, no work list)

@@ -103,7 +103,7 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
         // the centre of its bin lies inside the inscribed ball of the 3-bin cube, about a sixth of its volume, only
         // if the cube holds some 6 K points); where more such queries than the tile kernel hands over are expected,
         // the tile will go on to shell 2: 5 x ... x 5 columns of 5-bin runs.
-        const bool lonely = live && around < 4 * (a.k - 1);
+        const bool lonely = live && around < 4 * (a.slot0 + a.k_list);
         const bool goes_on = oct_sum_i32(lonely ? 1 : 0) * (kQueryBlock / kTileSamples) > a.defer_lanes;
         if (__any(goes_on)) {
             int32_t ncols2 = 1;
@@ -173,18 +173,12 @@ static void allow_lds(K kernel, size_t bytes)
     if (bytes > 48 * 1024) (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
-template <int D, int DB, bool COUNT>
-static hipError_t launch_query_impl(const QueryArgs& a_in, hipStream_t stream)
+// One pass of the fast path: tile kernel + list kernel for a.k_list <= 64 neighbours per query.
+template <int D, int DB, bool COUNT, bool LOWER>
+static void launch_query_pass(const QueryArgs& a_in, hipStream_t stream)
 {
     QueryArgs a = a_in;
     const int grid = (a.n + kQueryBlock - 1) / kQueryBlock;
-    const size_t heap_bytes = (size_t)(a.k > 1 ? a.k - 1 : 1) * kQueryBlock * sizeof(uint64_t);
-    if (a.algo == 1) {
-        allow_lds(k_query_shell<D, DB, COUNT>, heap_bytes);
-        hipLaunchKernelGGL((k_query_shell<D, DB, COUNT>), dim3(grid), dim3(kQueryBlock), heap_bytes, stream, a);
-        return hipGetLastError();
-    }
-    allow_lds(k_query_list<D, DB, COUNT>, heap_bytes);
     const bool ordered = a.tile_order && a.bin_idx && grid > 1024;    // a few waves per SIMD: nothing to reorder
     hipLaunchKernelGGL(k_reset_query_scratch, dim3(1), dim3(2 * kTileClasses), 0, stream, a.work_count,
                        ordered ? a.tile_order + 2 * grid : nullptr);
@@ -194,34 +188,50 @@ static hipError_t launch_query_impl(const QueryArgs& a_in, hipStream_t stream)
     } else {
         a.tile_order = nullptr;
     }
-    const int32_t cap = a.k - 1;
+    const int32_t cap = a.k_list;
     if (cap <= 16) {
         const size_t lds = tile_sorted_lds_bytes<16, D>();
-        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 16, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 16, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     } else if (cap <= 32) {
         const size_t lds = tile_sorted_lds_bytes<32, D>();
-        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 32, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 32, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     } else if (cap <= 48) {
         const size_t lds = tile_sorted_lds_bytes<48, D>();
-        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 48, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
-    } else if (cap <= 64) {
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 48, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
+    } else {
         const size_t lds = tile_sorted_lds_bytes<64, D>();
-        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 64, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
-    } else if (cap <= 96) {
-        const size_t lds = tile_sorted_lds_bytes<96, D>();
-        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 96, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
-    } else {
-        const size_t lds = tile_sorted_lds_bytes<128, D>();
-        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 128, COUNT>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 64, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     }
-    if (cap <= 64) {   // one query per wavefront
-        // four times the wave slots of the chip: the queries differ widely in cost, and with more, shorter
-        // workgroups the hardware dispatcher evens them out (cursors in memory cost more than they gained)
-        const int list_grid = a.n < 32768 ? a.n : 32768;
-        hipLaunchKernelGGL((k_query_list_wave<D, DB, COUNT>), dim3(list_grid), dim3(kQueryBlock), 0, stream, a);
-    } else {
-        const int list_grid = grid < 4096 ? grid : 4096;
-        hipLaunchKernelGGL((k_query_list<D, DB, COUNT>), dim3(list_grid), dim3(kQueryBlock), heap_bytes, stream, a);
+    // one query per wavefront; four times the wave slots of the chip: the queries differ widely in cost, and with
+    // more, shorter workgroups the hardware dispatcher evens them out (cursors in memory cost more than they gained)
+    const int list_grid = a.n < 32768 ? a.n : 32768;
+    hipLaunchKernelGGL((k_query_list_wave<D, DB, COUNT>), dim3(list_grid), dim3(kQueryBlock), 0, stream, a);
+}
+
+// Lists of more than 64 neighbours (K - 1 up to 127) take two passes: the first finds the 64 nearest, the second
+// the rest, counting only keys above the 64th (keys are unique, so the split is exact).  A sorted list of more
+// than 64 keys does not fit the 256 architectural registers of a wavefront next to everything else: held partly
+// in accumulation registers it ran at one wavefront per SIMD with a copy at every use, 2.8x slower per query at
+// K = 70 than at K = 65.
+template <int D, int DB, bool COUNT>
+static hipError_t launch_query_impl(const QueryArgs& a_in, hipStream_t stream)
+{
+    QueryArgs a = a_in;
+    if (a.algo == 1) {
+        const int grid = (a.n + kQueryBlock - 1) / kQueryBlock;
+        const size_t heap_bytes = (size_t)(a.k > 1 ? a.k - 1 : 1) * kQueryBlock * sizeof(uint64_t);
+        allow_lds(k_query_shell<D, DB, COUNT>, heap_bytes);
+        hipLaunchKernelGGL((k_query_shell<D, DB, COUNT>), dim3(grid), dim3(kQueryBlock), heap_bytes, stream, a);
+        return hipGetLastError();
+    }
+    const int32_t cap = a.k - 1;
+    a.slot0 = 0;
+    a.k_list = cap < 64 ? cap : 64;
+    launch_query_pass<D, DB, COUNT, false>(a, stream);
+    if (cap > 64) {
+        a.slot0 = 64;
+        a.k_list = cap - 64;
+        launch_query_pass<D, DB, COUNT, true>(a, stream);
     }
     return hipGetLastError();
 }

@@ -17,7 +17,7 @@
 // The tile kernel has already searched the first shells of every query it hands over: its list so
 // far sits in the query's output row and the first unsearched shell in slot 0 of the distance row,
 // so the search resumes there with a k-th best that already prunes most of the new shell.
-// Used for K-1 <= 64; larger K falls back to the one-lane-per-query list kernel.
+// A pass finds at most 64 neighbours; longer lists take two passes (see the launch code).
 #pragma once
 #include "fg_query.hpp"
 #include "fg_sortnet.hpp"
@@ -69,7 +69,7 @@ k_query_list_wave(QueryArgs a)
     __shared__ int32_t seg_excl[kQueryBlock], seg_a1[kQueryBlock], seg_len1[kQueryBlock], seg_a2[kQueryBlock];
     const int lane = threadIdx.x;
     const int32_t count = *a.work_count;
-    const int32_t cap = a.k - 1;                    // 1 <= cap <= 64 here
+    const int32_t cap = a.k_list;                   // 1 <= cap <= 64
     const uint64_t lt_mask = (1ull << lane) - 1;
 
     for (int32_t item = blockIdx.x; item < count; item += gridDim.x) {
@@ -81,9 +81,15 @@ k_query_list_wave(QueryArgs a)
         float* od = a.out_d2 + (int64_t)row * a.k;
         uint64_t best = 0ull;                       // ascending by lane; low lanes pinned
         if (lane >= kQueryBlock - cap) {
-            const int32_t j = lane - (kQueryBlock - cap) + 1;
+            const int32_t j = a.slot0 + lane - (kQueryBlock - cap) + 1;
             const int32_t bi = oi[j];
             best = bi < 0 ? kEmptyKey : (((uint64_t)__float_as_uint(od[j]) << 32) | (uint32_t)bi);
+        }
+        // second pass of a long list: only keys above the last one the first pass placed count
+        uint64_t lower = 0;
+        if (a.slot0 > 0) {
+            const int32_t li = oi[a.slot0];
+            lower = li < 0 ? kEmptyKey : (((uint64_t)__float_as_uint(od[a.slot0]) << 32) | (uint32_t)li);
         }
         const int32_t R0 = __float_as_int(od[0]);
         s.tau = __shfl(best, kQueryBlock - 1, 64);
@@ -194,7 +200,7 @@ k_query_list_wave(QueryArgs a)
                     const int32_t src = a.perm[q];
                     const bool live = in && q != p && !(a.dir && !dir_is_neighbour(a.dir[src]));
                     const uint64_t key = ((uint64_t)__float_as_uint(d2) << 32) | (uint32_t)src;
-                    const bool acc = live && key < s.tau;
+                    const bool acc = live && key < s.tau && (a.slot0 == 0 || key > lower);
                     if (COUNT) cand += __popcll(__ballot(live));
                     const uint64_t m = __ballot(acc);
                     if (m) {
@@ -212,7 +218,7 @@ k_query_list_wave(QueryArgs a)
         // output: slot 0 is the query itself, slot j >= 1 lives in lane 64 - cap + j - 1
         if (lane == 0) { oi[0] = row; od[0] = 0.0f; }
         if (lane >= kQueryBlock - cap) {
-            const int32_t j = lane - (kQueryBlock - cap) + 1;
+            const int32_t j = a.slot0 + lane - (kQueryBlock - cap) + 1;
             const bool real = best < kEmptyKey;
             oi[j] = real ? (int32_t)(uint32_t)best : -1;
             od[j] = real ? __uint_as_float((uint32_t)(best >> 32)) : 0.0f;

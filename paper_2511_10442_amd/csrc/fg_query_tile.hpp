@@ -14,7 +14,8 @@
 //     at the end of every shell, all lanes absorb their pending keys into the sorted register
 //     list with a fixed merging network (no data-dependent addressing, no LDS round trips);
 //   * keys are 64-bit (distance bits << 32 | original index); slots beyond K-1 are pinned with
-//     zero keys so that the last register is always the (K-1)-th best (list sizes 16/32/48/64/96/128);
+//     zero keys so that the last register is always the last wanted key (list sizes 16/32/48/64; longer
+//     lists take a second pass that counts only keys above the first pass's last one);
 //   * finished rows leave through LDS so that each output row is written as contiguous bytes;
 //   * lanes still uncertified when few are left are handed to the list kernel.
 #pragma once
@@ -29,11 +30,10 @@ namespace fg {
 // Waves per SIMD the register allocator aims at: the sorted list alone takes 2*KC registers.  Measured choices:
 // KC = 32 at three (two are 18 % slower, four spill into the scan loop and are slower too); KC = 48 at three for
 // d <= 3 (12 % faster than two although a few registers spill outside the loops; with d >= 4 a staged candidate
-// takes two more vector registers per unrolled slot and three waves lose 8 %); beyond 64 keys the list no longer
-// fits the 256 architectural registers of a wave and the kernel runs at one wave per SIMD.
+// takes two more vector registers per unrolled slot and three waves lose 8 %); 64 keys at two.
 template <int KC, int D> constexpr int tile_waves()
 {
-    return KC <= 16 ? 4 : (KC == 32 ? FG_TILE_WAVES32 : (KC == 48 ? (D <= 3 ? 3 : 2) : (KC <= 64 ? 2 : 1)));
+    return KC <= 16 ? 4 : (KC == 32 ? FG_TILE_WAVES32 : (KC == 48 ? (D <= 3 ? 3 : 2) : 2));
 }
 constexpr int kPend = 16;   // pending keys per lane between two merges
 struct Ranges { int32_t a1, b1, a2, b2; };
@@ -46,7 +46,7 @@ constexpr int kUnroll = 4;  // candidates per lane per pass of the scan loop (in
 // staged point = its D coordinates followed by its original index, padded to whole float4s
 template <int D> constexpr int stage_vecs() { return (D + 1 + 3) / 4; }
 
-template <int D, int DB, int KC, bool COUNT>
+template <int D, int DB, int KC, bool COUNT, bool LOWER>
 __global__ void __launch_bounds__(kQueryBlock) __attribute__((amdgpu_waves_per_eu(tile_waves<KC, D>(), tile_waves<KC, D>())))
 k_query_tile_sorted(QueryArgs a)
 {
@@ -65,7 +65,7 @@ k_query_tile_sorted(QueryArgs a)
     constexpr int NV = stage_vecs<D>();
     float4* stage = reinterpret_cast<float4*>(lds64 + kPend * kQueryBlock);   // [kStageChunk][NV]
 
-    const int32_t cap = a.k - 1;          // 0 <= cap <= KC
+    const int32_t cap = a.k_list;         // 0 <= cap <= KC
     const int32_t tile = a.tile_order ? a.tile_order[blockIdx.x] : (int32_t)blockIdx.x;   // heaviest tiles first
     const int32_t p = tile * kQueryBlock + lane;
     const bool valid = p < a.n;
@@ -74,6 +74,13 @@ k_query_tile_sorted(QueryArgs a)
     const int32_t my_row = a.perm[valid ? p : a.n - 1];
     const bool asks = !(a.dir && !dir_is_query(a.dir[my_row]));   // direction flag: does this point query at all
     bool active = valid && cap > 0 && asks;
+    // second pass of a long list (more than 64 neighbours): the first pass has placed the 64 nearest; only keys
+    // above the last of them count now (an empty slot there: the row split has no more points, nothing counts)
+    uint64_t lower = 0;
+    if (LOWER && active) {
+        const int32_t li = a.out_idx[(int64_t)my_row * a.k + a.slot0];
+        lower = li < 0 ? kEmptyKey : (((uint64_t)__float_as_uint(a.out_d2[(int64_t)my_row * a.k + a.slot0]) << 32) | (uint32_t)li);
+    }
 
 #ifdef FG_TILE_PROF
     const unsigned long long w_start = wall_clock64();
@@ -254,7 +261,7 @@ k_query_tile_sorted(QueryArgs a)
                         // kept if its distance does not exceed the k-th best's (a tie on the distance may lose
                         // on the index: the merge decides); NaN (poisoned) patterns lie above every bound
                         const uint32_t bits = __float_as_uint(d2);
-                        if (live && bits <= tau_hi) {
+                        if (live && bits <= tau_hi && (!LOWER || (((uint64_t)bits << 32) | __float_as_uint(w[u][D])) > lower)) {
                             // index word and distance word kPend planes apart, then the slot pointer moves on:
                             // written out because the compiler spends a third instruction on a register copy
                             static_assert(kPendHalf * 4 == 16 * 256 && kQueryBlock * 4 == 0x100, "offsets below");
@@ -311,12 +318,13 @@ k_query_tile_sorted(QueryArgs a)
     rows_lds[lane] = valid ? (asks ? my_row : -2 - my_row) : -1;   // -1: nothing to write; <= -2: all-padding row
     const uint32_t resume_word = (uint32_t)(R + 1);
 #ifndef FG_TILE_PROF
-    if (COUNT && valid) a.out_cand[my_row] = cand;
+    if (COUNT && valid) a.out_cand[my_row] = LOWER ? a.out_cand[my_row] + cand : cand;
 #endif
     const int32_t k = a.k;
-    const int32_t per_iter = k >= kQueryBlock ? 1 : kQueryBlock / k;    // rows written per pass
-    const int32_t sub = lane / k;                                       // which of them this lane serves
-    const int32_t j0 = lane - sub * k;                                  // slot inside the row
+    const int32_t kk = cap + 1;                                         // words written per row: slot 0 and this pass's slots
+    const int32_t per_iter = kk >= kQueryBlock ? 1 : kQueryBlock / kk;  // rows written per pass
+    const int32_t sub = lane / kk;                                      // which of them this lane serves
+    const int32_t j0 = lane - sub * kk;                                 // word inside the row
 #pragma unroll
     for (int pass = 0; pass < 2; ++pass) {
         if (pass) __syncthreads();
@@ -334,12 +342,13 @@ k_query_tile_sorted(QueryArgs a)
             const int32_t enc = rows_lds[ql];
             if (enc == -1) continue;
             const int32_t row = enc >= 0 ? enc : -2 - enc;
-            for (int32_t j = j0; j < k; j += kQueryBlock) {
+            for (int32_t j = j0; j < kk; j += kQueryBlock) {
                 uint32_t word = pass == 0 ? (enc >= 0 ? (uint32_t)row : 0xffffffffu) : 0u;   // slot 0: the row itself at distance 0
                 if (pass == 1 && ((mask >> ql) & 1)) word = resume_word;                     // handed over: where to resume
                 if (j > 0) word = dump[(KC - cap + j - 1) * kDumpStride + ql];
-                if (pass == 0) a.out_idx[(int64_t)row * k + j] = (int32_t)word;
-                else a.out_d2[(int64_t)row * k + j] = __uint_as_float(word);
+                const int32_t slot = j > 0 ? a.slot0 + j : 0;
+                if (pass == 0) a.out_idx[(int64_t)row * k + slot] = (int32_t)word;
+                else a.out_d2[(int64_t)row * k + slot] = __uint_as_float(word);
             }
         }
     }

@@ -62,6 +62,24 @@ def test_uniform_every_dimension(d):
         check_against_oracle(x, rs, k, nb, db, "d=%d k=%d nb=%d db=%d" % (d, k, nb, db))
 
 
+@pytest.mark.parametrize("k", [65, 66, 81, 97, 128])
+def test_long_lists_two_passes(k):
+    """More than 64 neighbours take two passes of the fast path (the second counts only keys above the
+    first pass's last one): the boundary cases, heavy ties across the boundary, duplicates of the query,
+    row splits shorter than K (padding in either pass), the candidate counts of both passes added up."""
+    x, rs = W.quantised(2600, 3, 5, seed=1200 + k, sizes=[1500, 70, 0, 1000, 30])     # ~21 points per location
+    check_against_oracle(x, rs, k, 0, 0, "quantised k=%d" % k)
+    check_against_oracle(x, rs, k, 6, 3, "quantised k=%d nb=6" % k)
+    x, rs = W.duplicates(1800, 2, 9, seed=1300 + k, sizes=[900, 900])                 # ~100 copies of each point
+    check_against_oracle(x, rs, k, 0, 0, "duplicates k=%d" % k)
+    x, rs = W.uniform(70_000, 3, seed=1400 + k, sizes=[40_000, 30_000])               # > 1024 tiles: ordered tiles
+    gi, gd, cand = gpu_knn(x, rs, k, counted=True)
+    rows = np.sort(np.random.Generator(np.random.PCG64(k)).choice(70_000, size=300, replace=False)).astype(np.int64)
+    oi, od = oracle.knn_rows(x, rs, k, rows)
+    assert_exact(gi[rows], gd[rows], oi, od, "uniform 70k k=%d" % k)
+    assert cand.min() >= k - 1 and cand.max() < 70_000
+
+
 @pytest.mark.parametrize("k", [2, 3, 16, 32, 40, 64, 100, 128])
 def test_k_range(k):
     x, rs = W.uniform(1500, 3, seed=800 + k, sizes=[1000, 500])
