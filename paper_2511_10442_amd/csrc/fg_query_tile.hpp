@@ -95,18 +95,24 @@ k_query_tile_sorted(QueryArgs a)
     uint64_t best[KC];
 #pragma unroll
     for (int i = 0; i < KC; ++i) best[i] = (i < KC - cap) ? 0ull : kEmptyKey;
+#pragma unroll
+    for (int i = 0; i < kPend; ++i) pend_lds[kPendHalf + i * kQueryBlock] = (uint32_t)(kEmptyKey >> 32);   // all pending slots empty
     int32_t cand = 0;
     int32_t useful = 0;   // candidates this lane evaluated
     int32_t passes = 0;   // scan passes of the wave (kUnroll lane slots each)
 
     auto absorb = [&]() {
         uint64_t pend[kPend];
+#ifdef FG_TILE_PROF
         const int32_t cnt = (int32_t)((pend_top - pend_base) / (kQueryBlock * 4));
+#endif
+        // unused slots hold the empty key's distance word (refilled below), whatever their index word: such keys
+        // lie at or above the empty key and sort behind every real one
 #pragma unroll
-        for (int i = 0; i < kPend; ++i) {
-            const uint64_t v = ((uint64_t)pend_lds[kPendHalf + i * kQueryBlock] << 32) | pend_lds[i * kQueryBlock];
-            pend[i] = i < cnt ? v : kEmptyKey;
-        }
+        for (int i = 0; i < kPend; ++i)
+            pend[i] = ((uint64_t)pend_lds[kPendHalf + i * kQueryBlock] << 32) | pend_lds[i * kQueryBlock];
+#pragma unroll
+        for (int i = 0; i < kPend; ++i) pend_lds[kPendHalf + i * kQueryBlock] = (uint32_t)(kEmptyKey >> 32);
         net_sort<kPend>(pend);
         net_absorb<KC, kPend>(best, pend);
 #ifdef FG_TILE_PROF
