@@ -222,3 +222,48 @@ def test_config5_backward():
     ref, asum = oracle.knn_backward(w.grad_d2, idx, w.coords)
     grad_close(backward_gpu(w.grad_d2, idx, w.coords, w.row_splits), ref, asum)
     _cache.clear()
+
+
+def test_output_larger_than_two_to_the_31_elements():
+    """The maximum-size case the interface allows in this memory: n * K beyond 2^31 output elements (row offsets must
+    be 64-bit everywhere) with a two-pass list (K - 1 > 64) over two row splits; forward rows sampled across the
+    whole range against the oracle, backward checked for the rows whose gradient the sample determines."""
+    n, d, k = 20_000_000, 3, 108
+    assert n * k > 2 ** 31
+    rng = np.random.Generator(np.random.PCG64(77))
+    x = rng.random((n, d), dtype=np.float32)
+    rs = np.array([0, n // 3, n], dtype=np.int32)
+    xt = torch.from_numpy(x).to(DEV)
+    rt = torch.from_numpy(rs).to(DEV)
+    idx, d2 = B.fg_binned_select_knn(xt, rt, k)
+    torch.cuda.synchronize()
+    rows = np.sort(np.concatenate([rng.choice(n, size=60, replace=False), [0, n // 3 - 1, n // 3, n - 1]])).astype(np.int64)
+    oi, od = oracle.knn_rows(x, rs, k, rows)
+    sel = torch.from_numpy(rows).to(DEV)
+    gi, gd = idx[sel].cpu().numpy(), d2[sel].cpu().numpy()
+    assert np.array_equal(gi, oi)
+    assert np.array_equal(gd.view(np.uint32), od.view(np.uint32))
+    # backward: a gradient only on the sampled rows' entries touches the sampled rows and their neighbours
+    g = torch.zeros((n, k), dtype=torch.float32, device=DEV)
+    g_rows = torch.from_numpy(rng.standard_normal((len(rows), k)).astype(np.float32)).to(DEV)
+    g[sel] = g_rows
+    grad = B.fg_knn_backward(g, idx, xt, rt)
+    torch.cuda.synchronize()
+    ref = {}
+    gr = g_rows.cpu().numpy().astype(np.float64)
+    for i, v in enumerate(rows):
+        for j in range(k):
+            u = int(oi[i, j])
+            if u < 0 or u == v:
+                continue
+            t = 2.0 * gr[i, j] * (x[v].astype(np.float64) - x[u].astype(np.float64))
+            ref[int(v)] = ref.get(int(v), 0.0) + t
+            ref[u] = ref.get(u, 0.0) - t
+    touched = np.array(sorted(ref.keys()), dtype=np.int64)
+    got = grad[torch.from_numpy(touched).to(DEV)].cpu().numpy().astype(np.float64)
+    want = np.stack([ref[int(t)] for t in touched])
+    scale = np.abs(want).max()
+    assert np.abs(got - want).max() <= 1e-5 * scale
+    assert float(grad.abs().sum().item()) > 0.0
+    total = float(grad.double().abs().sum().item())
+    assert abs(total - np.abs(got).sum()) <= 1e-6 * total       # nothing outside the touched rows
