@@ -47,8 +47,9 @@ constexpr size_t kAlign = 256;
 // Margins measured on uniform data (1e5..1e6 points, K = 10..100) and on the clustered
 // configurations.  For d <= 5 the bin width is ~1.1 r_K: finer grids are as fast or faster on
 // clustered data and for K >= 40, but for small K a large share of the queries then needs a
-// second shell and leaves the tile kernel.  d >= 6: ~0.6 r_K.
-constexpr double kTunedMarginByDim[11] = {0, 0, 0.9, 0.9, 0.9, 0.9, 1.6, 1.6, 1.6, 1.6, 1.6};
+// second shell and leaves the tile kernel.  d = 6: ~0.6 r_K (flat between 1.2 and 1.7); d >= 7: ~0.55 r_K
+// (1M uniform points, K = 40: d = 8 67 -> 54 ms, d = 10 243 -> 179 ms against 1.6; configuration 4 34 -> 28 ms).
+constexpr double kTunedMarginByDim[11] = {0, 0, 0.9, 0.9, 0.9, 0.9, 1.6, 1.85, 1.85, 1.85, 1.85};
 constexpr int32_t kTunedMaxBins = 1024;
 constexpr int32_t kDefaultDeferLanes = 6;
 constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
