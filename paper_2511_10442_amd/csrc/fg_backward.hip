@@ -98,49 +98,63 @@ template <int D> constexpr int bwd_slots() { return pow2_floor(FG_BWD_LDS_KB * 1
 template <int D> constexpr int bwd_rows() { return bwd_slots<D>() / FG_BWD_ROWS_DIV; }
 constexpr int ilog2(int v) { int b = 0; while ((1 << b) < v) ++b; return b; }
 
-// Adds kBwdBatch entries of one lane to the table (key u[e], D values each; u[e] < 0: nothing to add).
-// Open addressing with linear probing; the compare-and-swaps of one probe round are issued back to back
-// so that their round trips through the LDS overlap: those round trips, not the adds, are what the
-// table costs.
-template <int D>
-__device__ __forceinline__ void bwd_insert_batch(int32_t* keys, double* vals, const int32_t (&u)[kBwdBatch],
-                                                 const float (&t)[kBwdBatch][D], float* __restrict__ grad_coords)
+// Adds NE entries of one lane to the table (key u[e], D values each; u[e] < 0: nothing to add).
+// Open addressing with linear probing, in two phases.  First every entry finds its slot: rounds of
+// compare-and-swaps, those of one round issued back to back so that their round trips through the LDS
+// overlap, and an entry whose lanes are all settled issues nothing more.  Then the sums are added, one
+// instruction per entry and dim for the whole wave.  The LDS pipeline is what bounds this kernel and it
+// is paid per instruction, however few lanes take part: with the adds inside the probing rounds (issued
+// again in every round for the few lanes that settled in it) the kernel spent 2.3 times the LDS
+// instructions.
+template <int D, int NE>
+__device__ __forceinline__ void bwd_insert_batch(int32_t* keys, double* vals, const int32_t (&u)[NE],
+                                                 const float (&t)[NE][D], float* __restrict__ grad_coords)
 {
     constexpr int SLOTS = bwd_slots<D>();
-    uint32_t h[kBwdBatch];
-    bool open[kBwdBatch];
-    bool any_open = false;
+    uint32_t h[NE];
+    bool open[NE];
 #pragma unroll
-    for (int e = 0; e < kBwdBatch; ++e) {
+    for (int e = 0; e < NE; ++e) {
         h[e] = ((uint32_t)u[e] * 2654435761u) >> (32 - ilog2(SLOTS));
         open[e] = u[e] >= 0;
-        any_open = any_open || open[e];
     }
 #pragma unroll 1
-    for (int probe = 0; probe < kBwdProbes && any_open; ++probe) {
-        int32_t prev[kBwdBatch];
+    for (int probe = 0; probe < kBwdProbes; ++probe) {
+        bool any_open = false;
 #pragma unroll
-        for (int e = 0; e < kBwdBatch; ++e) prev[e] = open[e] ? atomicCAS(&keys[h[e]], -1, u[e]) : 0;
-        any_open = false;
+        for (int e = 0; e < NE; ++e) any_open = any_open || open[e];
+        if (!__any(any_open)) break;
+        int32_t prev[NE];
 #pragma unroll
-        for (int e = 0; e < kBwdBatch; ++e) {
+        for (int e = 0; e < NE; ++e) {
+            prev[e] = 0;
+            if (__any(open[e])) prev[e] = open[e] ? atomicCAS(&keys[h[e]], -1, u[e]) : 0;
+        }
+#pragma unroll
+        for (int e = 0; e < NE; ++e) {
             if (!open[e]) continue;
-            if (prev[e] == -1 || prev[e] == u[e]) {
-#pragma unroll
-                for (int c = 0; c < D; ++c) atomicAdd(&vals[c * SLOTS + h[e]], (double)t[e][c]);
-                open[e] = false;
-            } else {
-                h[e] = (h[e] + 1) & (SLOTS - 1);
-                any_open = true;
-            }
+            if (prev[e] == -1 || prev[e] == u[e]) open[e] = false;
+            else h[e] = (h[e] + 1) & (SLOTS - 1);
         }
     }
 #pragma unroll
-    for (int e = 0; e < kBwdBatch; ++e) {
-        if (!open[e]) continue;
+    for (int e = 0; e < NE; ++e) {
+        if (u[e] < 0) continue;
+        if (!open[e]) {
 #pragma unroll
-        for (int c = 0; c < D; ++c) atomicAdd(&grad_coords[(int64_t)u[e] * D + c], t[e][c]);
+            for (int c = 0; c < D; ++c) atomicAdd(&vals[c * SLOTS + h[e]], (double)t[e][c]);
+        } else {       // no slot within kBwdProbes probes: straight to global memory
+#pragma unroll
+            for (int c = 0; c < D; ++c) atomicAdd(&grad_coords[(int64_t)u[e] * D + c], t[e][c]);
+        }
     }
+}
+
+// value of lane l + N of the same 16-lane row (lanes past the row's end keep their own)
+template <int N>
+__device__ __forceinline__ float row16_from_above(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), 0x100 + N, 0xf, 0xf, false));   // row_shl:N
 }
 
 // One point's coordinates with as few load instructions as its row allows: the gathers of the
@@ -182,36 +196,48 @@ k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ 
     constexpr int ROWS = bwd_rows<D>();
     __shared__ int32_t keys[SLOTS];
     __shared__ double vals[D * SLOTS];
+    __shared__ int32_t rows_v[ROWS];       // the tile's rows (original indices), -1 past the end
+    const int64_t tile0 = (int64_t)blockIdx.x * ROWS;
     for (int i = threadIdx.x; i < SLOTS; i += bwd_block<D>()) keys[i] = -1;
     for (int i = threadIdx.x; i < D * SLOTS; i += bwd_block<D>()) vals[i] = 0.0;
+    for (int i = threadIdx.x; i < ROWS; i += bwd_block<D>()) rows_v[i] = tile0 + i < n ? perm[tile0 + i] : -1;
     __syncthreads();
 
     // A group of 16 lanes owns rows tile0 + sub, tile0 + sub + G, ... (G groups per block); lane l of the
     // group takes entries j = l, l + 16, ... of each.  The (row, 16-entry piece) pairs of a group are walked
-    // kBwdBatch at a time with all loads of a batch issued before any of its LDS work: the chain row ->
-    // index -> neighbour coordinates is three dependent trips to memory, and one chain at a time left the
-    // kernel waiting on them.
+    // kBwdBatch at a time.  The chain row -> index -> neighbour coordinates is three dependent trips to memory
+    // and one chain at a time left the kernel waiting on them: the rows come from LDS, the indices and upstream
+    // gradients of a batch are requested while the batch before it is worked on, and all coordinate loads of a
+    // batch are issued before any of its LDS work.
     constexpr int G = bwd_block<D>() / kLanesPerRow;
     constexpr int ROWS_PER_GROUP = ROWS / G;
     const int l = threadIdx.x % kLanesPerRow;
     const int sub = threadIdx.x / kLanesPerRow;
-    const int64_t tile0 = (int64_t)blockIdx.x * ROWS;
     const int32_t pieces = (k + kLanesPerRow - 1) / kLanesPerRow;
     const int32_t n_it = ROWS_PER_GROUP * pieces;
-    for (int32_t it0 = 0; it0 < n_it; it0 += kBwdBatch) {
-        int32_t v[kBwdBatch], u[kBwdBatch];
-        float g2[kBwdBatch];
+    int32_t v_next[kBwdBatch], u_next[kBwdBatch];
+    float g_next[kBwdBatch];
+    auto request = [&](int32_t it0) {
 #pragma unroll
         for (int e = 0; e < kBwdBatch; ++e) {
             const int32_t it = it0 + e;
             const int32_t ri = it / pieces;
             const int32_t j = (it - ri * pieces) * kLanesPerRow + l;
-            const int64_t pos = tile0 + (int64_t)ri * G + sub;
-            const bool live = it < n_it && pos < n;      // whole 16-lane groups are live or dead together
-            v[e] = live ? perm[pos] : -1;
-            const bool has = live && j < k;
-            u[e] = has ? idx[(int64_t)v[e] * k + j] : -1;
-            g2[e] = has ? 2.0f * grad_d2[(int64_t)v[e] * k + j] : 0.0f;
+            v_next[e] = it < n_it ? rows_v[ri * G + sub] : -1;      // whole 16-lane groups are live or dead together
+            const bool has = v_next[e] >= 0 && j < k;
+            u_next[e] = has ? idx[(int64_t)v_next[e] * k + j] : -1;
+            g_next[e] = has ? grad_d2[(int64_t)v_next[e] * k + j] : 0.0f;
+        }
+    };
+    request(0);
+    for (int32_t it0 = 0; it0 < n_it; it0 += kBwdBatch) {
+        int32_t v[kBwdBatch], u[kBwdBatch];
+        float g2[kBwdBatch];
+#pragma unroll
+        for (int e = 0; e < kBwdBatch; ++e) {
+            v[e] = v_next[e];
+            u[e] = u_next[e];
+            g2[e] = 2.0f * g_next[e];
             if (u[e] >= n || u[e] == v[e]) u[e] = -1;    // out of range: ignored; self contributes exactly 0
         }
         float xv[kBwdBatch][D], xu[kBwdBatch][D];
@@ -220,31 +246,64 @@ k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ 
             load_point<D, VEC>(coords, coords4, v[e] < 0 ? 0 : v[e], xv[e]);
             load_point<D, VEC>(coords, coords4, u[e] < 0 ? 0 : u[e], xu[e]);
         }
-        // neighbour side of the whole batch, then the rows' own side: each piece summed over its 16 lanes (one
-        // DPP row: four shifted adds leave the total in the row's last lane, no trip through the LDS crossbar)
-        // and added by that lane
-        float t[kBwdBatch][D];
-        int32_t own[kBwdBatch];
-#pragma unroll
-        for (int e = 0; e < kBwdBatch; ++e)
-#pragma unroll
-            for (int c = 0; c < D; ++c) t[e][c] = u[e] >= 0 ? g2[e] * (xu[e][c] - xv[e][c]) : 0.0f;
-        bwd_insert_batch<D>(keys, vals, u, t, grad_coords);
+        request(it0 + kBwdBatch);
+        // One insertion for the neighbour side of the whole batch and the rows' own side.  Own side: each piece
+        // summed over its 16 lanes (one DPP row: four shifted adds leave the total in the row's last lane, no
+        // trip through the LDS crossbar); pieces of one row are added up first; then the batch's own sums move
+        // from the last lane to lanes 15, 14, ... of the row, one per lane, so that they are a single table
+        // entry per lane instead of kBwdBatch entries with a sixteenth of the lanes each.
+        static_assert(kBwdBatch <= 4, "own sums are spread over the last four lanes of a row");
+        int32_t key[kBwdBatch + 1];
+        float t[kBwdBatch + 1][D];
+        float own[kBwdBatch][D];
+        bool own_live[kBwdBatch];
 #pragma unroll
         for (int e = 0; e < kBwdBatch; ++e) {
+            key[e] = u[e];
 #pragma unroll
-            for (int c = 0; c < D; ++c) t[e][c] = row16_sum_to_last(-t[e][c]);
-            own[e] = l == kLanesPerRow - 1 ? v[e] : -1;
+            for (int c = 0; c < D; ++c) {
+                t[e][c] = u[e] >= 0 ? g2[e] * (xu[e][c] - xv[e][c]) : 0.0f;
+                own[e][c] = -t[e][c];
+            }
+            own_live[e] = v[e] >= 0;
         }
-        bwd_insert_batch<D>(keys, vals, own, t, grad_coords);
+#pragma unroll
+        for (int e = 1; e < kBwdBatch; ++e) {
+            if (v[e] >= 0 && v[e] == v[e - 1]) {      // next piece of the same row (the same in all 16 lanes)
+#pragma unroll
+                for (int c = 0; c < D; ++c) own[e][c] += own[e - 1][c];
+                own_live[e - 1] = false;
+            }
+        }
+        key[kBwdBatch] = -1;
+#pragma unroll
+        for (int c = 0; c < D; ++c) t[kBwdBatch][c] = 0.0f;
+#pragma unroll
+        for (int e = 0; e < kBwdBatch; ++e) {
+            float moved[D];
+#pragma unroll
+            for (int c = 0; c < D; ++c) {
+                const float total = row16_sum_to_last(own[e][c]);
+                moved[c] = e == 0 ? total : e == 1 ? row16_from_above<1>(total) : e == 2 ? row16_from_above<2>(total)
+                                                                                         : row16_from_above<3>(total);
+            }
+            if (l == kLanesPerRow - 1 - e) {
+                key[kBwdBatch] = own_live[e] ? v[e] : -1;
+#pragma unroll
+                for (int c = 0; c < D; ++c) t[kBwdBatch][c] = moved[c];
+            }
+        }
+        bwd_insert_batch<D, kBwdBatch + 1>(keys, vals, key, t, grad_coords);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < SLOTS; i += bwd_block<D>()) {
-        const int32_t u = keys[i];
-        if (u >= 0) {
-#pragma unroll
-            for (int c = 0; c < D; ++c) atomicAdd(&grad_coords[(int64_t)u * D + c], (float)vals[c * SLOTS + i]);
-        }
+    // flush: the D sums of a destination go out from neighbouring lanes, so that they reach the memory side as
+    // one request per destination row instead of one per float
+    constexpr int LPS = D <= 2 ? 2 : (D <= 4 ? 4 : (D <= 8 ? 8 : 16));   // lanes per slot
+    for (int i = threadIdx.x; i < SLOTS * LPS; i += bwd_block<D>()) {
+        const int slot = i / LPS, c = i % LPS;
+        const int32_t u = keys[slot];
+        if (u >= 0 && c < D)
+            atomicAdd(&grad_coords[(int64_t)u * D + c], (float)vals[c * SLOTS + slot]);
     }
 }
 
