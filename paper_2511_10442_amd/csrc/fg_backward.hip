@@ -75,8 +75,10 @@ __device__ __forceinline__ float row16_sum_to_last(float v)
 // probes go straight to global memory, so the table size bounds nothing but speed.
 // Sizes, all measured on the 1M-point d = 3 K = 32 workload: 1024 threads per block and two blocks per CU (the
 // kernel waits on chains of dependent loads, row -> index -> coordinates, and on LDS round trips, so it wants
-// every wave slot filled: 256-thread blocks with the same table were 35 % slower); four table slots per row
-// (a tile's rows reach about two distinct destinations each).
+// every wave slot filled: 256-thread blocks with the same table were 35 % slower); eight table slots per row
+// (a tile's rows reach two to three distinct destinations each, and a table a third full settles nearly every
+// entry in the first probing round; with four slots per row the larger tile saved memory-side requests in
+// the flush but lost more in probing rounds: 0.378 against 0.355 ms).
 constexpr int kBwdProbes = 12;
 #ifndef FG_BWD_BATCH
 #define FG_BWD_BATCH 4
@@ -93,7 +95,7 @@ constexpr int pow2_floor(int v) { int p = 1; while (2 * p <= v) p *= 2; return p
 // table slots: the largest power of two whose keys (4 bytes) and D double sums fit the LDS budget of a block
 template <int D> constexpr int bwd_slots() { return pow2_floor(FG_BWD_LDS_KB * 1024 / (4 + 8 * D)); }
 #ifndef FG_BWD_ROWS_DIV
-#define FG_BWD_ROWS_DIV 4
+#define FG_BWD_ROWS_DIV 8
 #endif
 template <int D> constexpr int bwd_rows() { return bwd_slots<D>() / FG_BWD_ROWS_DIV; }
 constexpr int ilog2(int v) { int b = 0; while ((1 << b) < v) ++b; return b; }
@@ -211,6 +213,7 @@ k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ 
     // batch are issued before any of its LDS work.
     constexpr int G = bwd_block<D>() / kLanesPerRow;
     constexpr int ROWS_PER_GROUP = ROWS / G;
+    static_assert(ROWS_PER_GROUP >= 1 && ROWS_PER_GROUP * G == ROWS, "a tile is a whole number of rows per 16-lane group");
     const int l = threadIdx.x % kLanesPerRow;
     const int sub = threadIdx.x / kLanesPerRow;
     const int32_t pieces = (k + kLanesPerRow - 1) / kLanesPerRow;
