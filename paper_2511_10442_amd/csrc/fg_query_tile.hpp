@@ -47,6 +47,32 @@ constexpr int kUnroll = 4;  // candidates per lane per pass of the scan loop (in
 // staged point = its D coordinates followed by its original index, padded to whole float4s
 template <int D> constexpr int stage_vecs() { return (D + 1 + 3) / 4; }
 
+// One whole output row from the lane that holds it: word 0 and the keys best[OFF ...], as 16-byte stores.
+// The row has KC - OFF + 1 words, a multiple of four, and starts on a 16-byte boundary.
+template <int KC, int OFF>
+__device__ __forceinline__ void store_row_from_registers(const uint64_t (&best)[KC], int32_t* __restrict__ oi,
+                                                         float* __restrict__ od, int32_t idx0, uint32_t d2_0)
+{
+    constexpr int WORDS = KC - OFF + 1;
+    static_assert(WORDS % 4 == 0 && OFF >= 1, "whole 16-byte pieces");
+#pragma unroll
+    for (int c = 0; c < WORDS / 4; ++c) {
+        int32_t wi[4];
+        uint32_t wd[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int j = 4 * c + t;
+            if (j == 0) { wi[t] = idx0; wd[t] = d2_0; continue; }
+            const uint64_t key = best[OFF + j - 1];
+            const bool real = key < kEmptyKey;
+            wi[t] = real ? (int32_t)(uint32_t)key : -1;
+            wd[t] = real ? (uint32_t)(key >> 32) : 0u;
+        }
+        reinterpret_cast<int4*>(oi)[c] = make_int4(wi[0], wi[1], wi[2], wi[3]);
+        reinterpret_cast<uint4*>(od)[c] = make_uint4(wd[0], wd[1], wd[2], wd[3]);
+    }
+}
+
 template <int D, int DB, int KC, bool COUNT, bool LOWER>
 __global__ void __launch_bounds__(kQueryBlock) __attribute__((amdgpu_waves_per_eu(tile_waves<KC, D>(), tile_waves<KC, D>())))
 k_query_tile_sorted(QueryArgs a)
@@ -322,14 +348,33 @@ k_query_tile_sorted(QueryArgs a)
         if (active) a.work_list[base + __popcll(mask & ((1ull << lane) - 1))] = p;
     }
 
-    // finished rows: registers -> LDS -> contiguous row writes
     PROF_T0
+    const uint32_t resume_word = (uint32_t)(R + 1);
+    // Rows of exactly KC words (K = 16, 32, 48, 64) leave straight from the registers: every lane writes its own
+    // row in 16-byte pieces (the pieces of a 128-byte line arrive within a few instructions of each other and are
+    // joined in the L2 cache).  A sixteenth of the instructions of the transposition below: query stage -8 % at
+    // K = 16, -4 % at K = 32, +-0 at K = 64.  Rows that do not start on a 64-byte boundary (K = 40: 160 bytes)
+    // were 3 % slower this way and keep the transposition.
+    const bool direct_rows = a.slot0 == 0 && a.k == KC && cap == KC - 1 &&
+                             (((uintptr_t)a.out_idx | (uintptr_t)a.out_d2) & 15) == 0;
+    if (direct_rows) {
+#ifndef FG_TILE_PROF
+        if (COUNT && valid) a.out_cand[my_row] = LOWER ? a.out_cand[my_row] + cand : cand;
+#endif
+        if (valid) {
+            int32_t* oi = a.out_idx + (int64_t)my_row * a.k;
+            float* od = a.out_d2 + (int64_t)my_row * a.k;
+            const int32_t idx0 = asks ? my_row : -1;
+            const uint32_t d2_0 = ((mask >> lane) & 1) ? resume_word : 0u;     // handed over: where to resume
+            store_row_from_registers<KC, 1>(best, oi, od, idx0, d2_0);
+        }
+    } else {
+    // otherwise: registers -> LDS -> contiguous row writes
     __syncthreads();
     // two passes (indices, then distances) so the transposition needs KC x 64 words, not keys
     int32_t* rows_lds = reinterpret_cast<int32_t*>(lds64);
     uint32_t* dump = reinterpret_cast<uint32_t*>(lds64) + kQueryBlock;     // [KC][64] after the 64 row words
     rows_lds[lane] = valid ? (asks ? my_row : -2 - my_row) : -1;   // -1: nothing to write; <= -2: all-padding row
-    const uint32_t resume_word = (uint32_t)(R + 1);
 #ifndef FG_TILE_PROF
     if (COUNT && valid) a.out_cand[my_row] = LOWER ? a.out_cand[my_row] + cand : cand;
 #endif
@@ -364,6 +409,7 @@ k_query_tile_sorted(QueryArgs a)
                 else a.out_d2[(int64_t)row * k + slot] = __uint_as_float(word);
             }
         }
+    }
     }
 #ifdef FG_TILE_PROF
     PROF_ADD(t_out)
