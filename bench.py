@@ -4,9 +4,10 @@
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 3] [--n-bins N] [--d-bin D]
 
 A step is one pass of the whole hot path over one batch of synthetic input already resident
-in HBM: bounding box + bin assignment + counting sort + exact shell-expanding query
-(fg_binned_select_knn) followed by the backward scatter (fg_knn_backward) when the
-configuration has a backward pass.  The headline workload is configuration 3: 1,000,000
+in HBM: bounding box + bin assignment + counting sort (fg_bin_points), the exact
+shell-expanding query on that binning (fg_query_binned; the two together are what
+fg_binned_select_knn runs) and, when the configuration has a backward pass, the backward
+scatter in the same bin order (fg_knn_backward_binned: a training step bins its points once).  The headline workload is configuration 3: 1,000,000
 points, d = 3, 10 row splits, K = 32.  One JSON line is printed on stdout.
 
 Besides the contract fields the line carries
@@ -84,9 +85,10 @@ def main() -> int:
     grad = torch.empty((n, d), dtype=torch.float32, device=dev) if w.backward else None
 
     def step():
-        B.fg_binned_select_knn(x, rs, k, args.n_bins, args.d_bin, ws, out_idx, out_d2)
+        binning = B.fg_bin_points(x, rs, k, args.n_bins, args.d_bin, ws)
+        B.fg_query_binned(binning, rs, k, out_idx, out_d2)
         if w.backward:
-            B.fg_knn_backward(g, out_idx, x, rs, grad, ws)
+            B.fg_knn_backward_binned(binning, g, out_idx, x, grad)
 
     for _ in range(args.warmup):
         step()
@@ -121,8 +123,9 @@ def main() -> int:
     torch.cuda.synchronize()
     total_cand = int(cand.to(torch.int64).sum().item())
     deferred = int(binning.work_count.item())
-    # the backward re-bins into the same workspace, so `binning` is dead from here on
-    ms_bwd = timed(lambda: B.fg_knn_backward(g, out_idx, x, rs, grad, ws), reps) if w.backward else None
+    ms_bwd = timed(lambda: B.fg_knn_backward_binned(binning, g, out_idx, x, grad), reps) if w.backward else None
+    # the stand-alone backward bins once more, into the same workspace: `binning` is dead from here on
+    ms_bwd_alone = timed(lambda: B.fg_knn_backward(g, out_idx, x, rs, grad, ws), reps) if w.backward else None
 
     total_bins = binning.n_segments * binning.cells_per_segment
     algo_bytes = n * (k * 8 + d * 4 + 4) + (total_bins + 1) * 4
@@ -161,12 +164,13 @@ def main() -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": w.note, "name": w.name, "n": n, "d": d, "k": k, "segments": s,
                    "n_bins": binning.n_bins, "d_bin": binning.d_bin,
-                   "step": "fg_binned_select_knn" + (" + fg_knn_backward" if w.backward else "")},
+                   "step": "fg_bin_points + fg_query_binned" + (" + fg_knn_backward_binned" if w.backward else "")},
         "roofline": roofline,
         "roofline_alu": roofline_alu,
         "cpu_baseline": cpu,
         "stages": {"binning_ms": round(ms_bin, 4), "query_ms": round(ms_query, 4),
                    "backward_ms": None if ms_bwd is None else round(ms_bwd, 4),
+                   "backward_standalone_ms": None if ms_bwd_alone is None else round(ms_bwd_alone, 4),
                    "query_only_queries_per_s": round(n / (ms_query * 1e-3), 1),
                    "candidates_per_query": round(total_cand / n, 2),
                    "queries_handed_to_list_kernel": deferred,

@@ -170,6 +170,16 @@ fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float*
                           const int32_t* row_splits, int64_t n, int32_t d, int32_t n_segments, int32_t k,
                           float* grad_coords, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same backward on an existing binning (Section 3: the points are sorted by their bins once; the training
+ * step that ran the forward on these points has that order already).  `view` must come from fg_bin_points on the
+ * same coords, and the workspace it points into must not have been written since, except by fg_query_binned.
+ * Its bin order is the row order; nothing is binned again (on 1M points the re-binning is a quarter of
+ * fg_knn_backward's time).  Arguments, result and error behaviour as for fg_knn_backward; view == NULL or a view
+ * without a row order is FG_ERR_NULL. */
+fg_status fg_knn_backward_binned(const fg_binning* view, const float* grad_d2, const int32_t* idx,
+                                 const float* coords, int64_t n, int32_t d, int32_t k, float* grad_coords,
+                                 void* stream);
+
 /* Object-condensation index matrices (Section 5, Algorithm 3).
  *   asso_idx       [n_vert] int32  object id each vertex is associated with (any value that is no object id,
  *                                  e.g. -1, means none)

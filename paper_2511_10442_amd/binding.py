@@ -24,7 +24,7 @@ FG_ERR_LAUNCH = 5
 
 EXPORTS = ["fg_status_string", "fg_auto_n_bins", "fg_workspace_size", "fg_bin_points",
            "fg_binned_select_knn", "fg_binned_select_knn_dir", "fg_binned_select_knn_counted", "fg_query_binned",
-           "fg_knn_backward", "fg_oc_helper", "fg_oc_helper_workspace_size"]
+           "fg_knn_backward", "fg_knn_backward_binned", "fg_oc_helper", "fg_oc_helper_workspace_size"]
 
 
 class FgError(RuntimeError):
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
         L.fg_query_binned.argtypes = [ctypes.POINTER(_Binning), vp, i64, i32, i32, i32, vp, vp, vp, vp]
         L.fg_knn_backward.restype = ctypes.c_int
         L.fg_knn_backward.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, vp, vp, sz, vp]
+        L.fg_knn_backward_binned.restype = ctypes.c_int
+        L.fg_knn_backward_binned.argtypes = [ctypes.POINTER(_Binning), vp, vp, vp, i64, i32, i32, vp, vp]
         L.fg_oc_helper.restype = ctypes.c_int
         L.fg_oc_helper.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
         L.fg_oc_helper_workspace_size.restype = ctypes.c_int
@@ -293,6 +295,23 @@ def fg_knn_backward(grad_d2: torch.Tensor, idx: torch.Tensor, coords: torch.Tens
     _check(lib().fg_knn_backward(_ptr(grad_d2), _ptr(idx), _ptr(coords), _ptr(row_splits), n, d, s, k,
                                  _ptr(grad_coords), _ptr(workspace),
                                  0 if workspace is None else workspace.numel(), _stream()), "fg_knn_backward")
+    return grad_coords
+
+
+def fg_knn_backward_binned(binning: Binning, grad_d2: torch.Tensor, idx: torch.Tensor, coords: torch.Tensor,
+                           grad_coords: torch.Tensor | None = None) -> torch.Tensor:
+    """Backward on the binning the forward used (fg_bin_points on the same coords, workspace untouched since)."""
+    grad_d2 = _dev(grad_d2, torch.float32, "grad_d2")
+    idx = _dev(idx, torch.int32, "idx")
+    coords = _dev(coords, torch.float32, "coords")
+    n, d = coords.shape
+    k = idx.shape[1]
+    if tuple(grad_d2.shape) != (n, k) or idx.shape[0] != n or n != binning.n or d != binning.d:
+        raise ValueError("grad_d2 and idx must be [n, k] for the binned coords [n, d]")
+    if grad_coords is None:
+        grad_coords = torch.empty((n, d), dtype=torch.float32, device=coords.device)
+    _check(lib().fg_knn_backward_binned(ctypes.byref(binning.raw), _ptr(grad_d2), _ptr(idx), _ptr(coords), n, d, k,
+                                        _ptr(grad_coords), _stream()), "fg_knn_backward_binned")
     return grad_coords
 
 

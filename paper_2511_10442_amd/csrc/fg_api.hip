@@ -352,6 +352,22 @@ fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float*
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }
 
+fg_status fg_knn_backward_binned(const fg_binning* view, const float* grad_d2, const int32_t* idx,
+                                 const float* coords, int64_t n, int32_t d, int32_t k, float* grad_coords,
+                                 void* stream)
+{
+    if (!view) return FG_ERR_NULL;
+    fg_status st = check_problem(n, d, 1, k);
+    if (st != FG_OK) return st;
+    if (n == 0) return FG_OK;
+    if (!grad_d2 || !idx || !coords || !grad_coords || !view->perm) return FG_ERR_NULL;
+    // the forward's bin order (runs of bins along the last binning dimension) is a little less compact than the
+    // bit-interleaved order fg_knn_backward makes for itself: +0.01 ms in the kernel against 0.08 ms of binning
+    hipError_t e = launch_backward(grad_d2, idx, coords, nullptr, view->perm, (int32_t)n, d, k, grad_coords,
+                                   (hipStream_t)stream);
+    return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
+}
+
 fg_status fg_oc_helper_workspace_size(int64_t n_unique, int32_t n_maxrs, size_t* bytes)
 {
     if (!bytes) return FG_ERR_NULL;

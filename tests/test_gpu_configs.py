@@ -110,6 +110,17 @@ def backward_gpu(g, idx, x, rs):
     return out.cpu().numpy()
 
 
+def backward_binned_gpu(g, idx, x, rs, k):
+    """The bench's launch configuration: backward in the bin order of the forward's binning."""
+    xt, rst = torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV)
+    ws = B.alloc_workspace(x.shape[0], x.shape[1], len(rs) - 1, k, 0, 0, DEV)
+    binning = B.fg_bin_points(xt, rst, k, 0, 0, ws)
+    out = B.fg_knn_backward_binned(binning, torch.from_numpy(g).to(DEV),
+                                   torch.from_numpy(np.ascontiguousarray(idx)).to(DEV), xt)
+    torch.cuda.synchronize()
+    return out.cpu().numpy()
+
+
 def sampled_graph(w, rows):
     """[n,k] index matrix whose sampled rows are the oracle's neighbours and every other row is padding."""
     oi, od = oracle.knn_rows(w.coords, w.row_splits, w.k, rows)
@@ -164,6 +175,12 @@ def test_config3_forward():
     check_digests(3, gi, gd)
     gi2, gd2 = forward(w, 30, 3)                                 # the paper's clamped bin count
     assert np.array_equal(gi2, gi) and np.array_equal(gd2.view(np.uint32), gd.view(np.uint32))
+    # the two calls bench.py times (bin, then query on that binning)
+    xt, rst = torch.from_numpy(w.coords).to(DEV), torch.from_numpy(w.row_splits).to(DEV)
+    ws = B.alloc_workspace(w.n, w.d, w.n_segments, w.k, 0, 0, DEV)
+    gi3, gd3 = B.fg_query_binned(B.fg_bin_points(xt, rst, w.k, 0, 0, ws), rst, w.k)
+    torch.cuda.synchronize()
+    assert np.array_equal(gi3.cpu().numpy(), gi) and np.array_equal(gd3.cpu().numpy().view(np.uint32), gd.view(np.uint32))
 
 
 def test_config3_backward():
@@ -172,9 +189,11 @@ def test_config3_backward():
     idx, _, _ = sampled_graph(w, rows)
     ref, asum = oracle.knn_backward(w.grad_d2, idx, w.coords)
     grad_close(backward_gpu(w.grad_d2, idx, w.coords, w.row_splits), ref, asum)
+    grad_close(backward_binned_gpu(w.grad_d2, idx, w.coords, w.row_splits, w.k), ref, asum)
     idx = random_in_segment_graph(w, seed=323)
     ref, asum = oracle.knn_backward(w.grad_d2, idx, w.coords)
     grad_close(backward_gpu(w.grad_d2, idx, w.coords, w.row_splits), ref, asum)
+    grad_close(backward_binned_gpu(w.grad_d2, idx, w.coords, w.row_splits, w.k), ref, asum)
 
 
 def test_config4_forward():

@@ -310,6 +310,25 @@ def test_backward_small(d, k):
     grad_close(gpu_backward(g, idx, x, rs), ref, asum)
 
 
+@pytest.mark.parametrize("d,k", [(2, 16), (3, 32), (5, 40), (8, 7)])
+def test_backward_on_the_forward_binning(d, k):
+    """Bin once, query, backward in the same bin order: the gradient of the graph just built."""
+    sizes = [900, 2, 1300]
+    n = sum(sizes)
+    x, rs = W.uniform(n, d, seed=71 + d, sizes=sizes)
+    xt, rst = torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV)
+    ws = B.alloc_workspace(n, d, len(sizes), k, 0, 0, DEV)
+    binning = B.fg_bin_points(xt, rst, k, 0, 0, ws)
+    gi, gd = B.fg_query_binned(binning, rst, k)
+    g = W.upstream_grad(n, k, seed=73)
+    out = B.fg_knn_backward_binned(binning, torch.from_numpy(g).to(DEV), gi, xt)
+    torch.cuda.synchronize()
+    oi, _ = oracle.knn(x, rs, k)
+    assert np.array_equal(gi.cpu().numpy(), oi)
+    ref, asum = oracle.knn_backward(g, oi, x)
+    grad_close(out.cpu().numpy(), ref, asum)
+
+
 def test_backward_hash_table_overflow_and_hot_destination():
     """More distinct destinations per block than the LDS table holds (random far neighbours), and one
     destination shared by every row: both must still add up."""
