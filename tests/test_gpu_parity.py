@@ -87,6 +87,27 @@ def test_k_range(k):
     check_against_oracle(x, rs, k, 9, 3, "k=%d nb=9" % k)
 
 
+@pytest.mark.parametrize("k", [16, 32, 48, 64])
+def test_rows_written_from_registers_and_through_the_transposition(k):
+    """Rows of exactly the list size leave the tile kernel as 16-byte stores when the output is
+    16-byte aligned, through LDS otherwise: same result, nothing written outside the rows."""
+    x, rs = W.uniform(2100, 3, seed=900 + k, sizes=[1500, 7, 593])          # a short split: padded rows
+    n = x.shape[0]
+    xt, rt = torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV)
+    oi, od = oracle.knn(x, rs, k)
+    for shift in (0, 1):                                                     # shift 1: 4 bytes off alignment
+        base_i = torch.full((n * k + 8,), -7, dtype=torch.int32, device=DEV)
+        base_d = torch.full((n * k + 8,), -7.0, dtype=torch.float32, device=DEV)
+        out_i = base_i[4 + shift:4 + shift + n * k].view(n, k)
+        out_d = base_d[4 + shift:4 + shift + n * k].view(n, k)
+        B.fg_binned_select_knn(xt, rt, k, 0, 0, None, out_i, out_d)
+        torch.cuda.synchronize()
+        assert_exact(out_i.cpu().numpy(), out_d.cpu().numpy(), oi, od, "k=%d shift=%d" % (k, shift))
+        guard_i, guard_d = base_i.cpu().numpy(), base_d.cpu().numpy()
+        assert np.all(guard_i[:4 + shift] == -7) and np.all(guard_i[4 + shift + n * k:] == -7)
+        assert np.all(guard_d[:4 + shift] == -7.0) and np.all(guard_d[4 + shift + n * k:] == -7.0)
+
+
 def test_n_bins_invariance():
     x, rs = W.uniform(3000, 3, seed=77, sizes=[1800, 1200])
     oi, od = oracle.knn(x, rs, 12)
