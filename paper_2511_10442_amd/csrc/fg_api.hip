@@ -272,7 +272,7 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
     a.row_splits = row_splits; a.dir = view->dir; a.out_idx = out_idx; a.out_d2 = out_d2; a.out_cand = out_candidates;
     a.soa_stride = view->soa_stride; a.n = (int32_t)n; a.n_segments = n_segments; a.k = k;
     a.n_bins = view->n_bins; a.cells_per_segment = (int32_t)view->cells_per_segment;
-    a.work_list = view->work_list; a.work_count = view->work_count; a.bin_idx = view->bin_idx; a.tile_order = view->tile_order; a.algo = view->query_algo == 1 ? 1 : 0;
+    a.work_list = view->work_list; a.work_count = view->work_count; a.bin_idx = view->bin_idx; a.tile_order = view->tile_order; a.algo = (view->query_algo == 1 || view->query_algo == 2) ? view->query_algo : 0;
     a.defer_lanes = view->defer_lanes < 0 ? 0 : (view->defer_lanes > 64 ? 64 : view->defer_lanes);
     hipError_t e = launch_query(a, d, view->d_bin, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;

@@ -296,6 +296,17 @@ __device__ __forceinline__ int32_t wave_sum_i32(int32_t v)
     v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);
     return __builtin_amdgcn_readlane(v, 63);
 }
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ int32_t wave_incl_scan_dpp_i32(int32_t v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);
+    return v;
+}
 __device__ __forceinline__ int32_t wave_max_i32(int32_t v)
 {
     const int32_t id = (int32_t)0x80000000;

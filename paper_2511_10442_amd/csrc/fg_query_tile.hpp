@@ -73,13 +73,22 @@ __device__ __forceinline__ void store_row_from_registers(const uint64_t (&best)[
     }
 }
 
-template <int D, int DB, int KC, bool COUNT, bool LOWER>
-__global__ void __launch_bounds__(kQueryBlock) __attribute__((amdgpu_waves_per_eu(tile_waves<KC, D>(), tile_waves<KC, D>())))
-k_query_tile_sorted(QueryArgs a)
+constexpr int kTileFlatBit = 6;   // in a tile's class word: the ordering kernels found the tile uneven
+constexpr int kOrderFlagBit = 30;  // the same flag in the tile's entry of the order (tiles number below 2^25)
+#ifndef FG_FLAT_CHUNK
+#define FG_FLAT_CHUNK 96
+#endif
+// Points staged per chunk by the flattened scan: its extra LDS comes out of the stage, so that a workgroup needs
+// no more than the direct scan's and three wavefronts per SIMD still fit a CU's 160 KB (with 160 points, 0.8 KB more
+// per workgroup, every tile ran at 11 wavefronts per CU instead of 12: +7 % on even data).
+constexpr int kFlatChunk = FG_FLAT_CHUNK;
+
+template <int D, int DB, int KC, bool COUNT, bool LOWER, bool FLAT>
+__device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile, uint64_t* lds64)
 {
+    constexpr int CHUNK = FLAT ? kFlatChunk : kStageChunk;
     // LDS: [pending kPend x 64 keys][stage (D+1) x kStageChunk words]; re-used at the end as
     //      [rows 64 words][KC x 64 words of the sorted lists, indices first, distances second]
-    extern __shared__ uint64_t lds64[];
     const int lane = threadIdx.x;
     // pending keys: index words [kPend][64], then distance words [kPend][64]
     uint32_t* const pend_lds = reinterpret_cast<uint32_t*>(lds64) + lane;
@@ -91,9 +100,16 @@ k_query_tile_sorted(QueryArgs a)
     uint32_t pend_top = pend_base;
     constexpr int NV = stage_vecs<D>();
     float4* stage = reinterpret_cast<float4*>(lds64 + kPend * kQueryBlock);   // [kStageChunk][NV]
+    // flattened scan only: after the stage, [64][NV] the queries (coordinates, then the distance word of the k-th
+    // best), [64] pending counts, [64] run descriptors, [66] run starts in the flattened order, [64] lower bounds
+    float4* const qx = stage + (CHUNK + kUnroll) * NV;
+    uint32_t* const pend_cnt = reinterpret_cast<uint32_t*>(qx + kQueryBlock * NV);
+    int32_t* const fl_info = reinterpret_cast<int32_t*>(pend_cnt + kQueryBlock);
+    int32_t* const fl_start = fl_info + kQueryBlock;
+    uint64_t* const qlower = reinterpret_cast<uint64_t*>(fl_start + kQueryBlock + 2);
+    const uint64_t lt_mask = (1ull << lane) - 1;
 
     const int32_t cap = a.k_list;         // 0 <= cap <= KC
-    const int32_t tile = a.tile_order ? a.tile_order[blockIdx.x] : (int32_t)blockIdx.x;   // heaviest tiles first
     const int32_t p = tile * kQueryBlock + lane;
     const bool valid = p < a.n;
     LaneGeom<D, DB> s;
@@ -112,7 +128,7 @@ k_query_tile_sorted(QueryArgs a)
 #ifdef FG_TILE_PROF
     const unsigned long long w_start = wall_clock64();
     long long t_all = clock64(), t_setup = 0, t_stage = 0, t_scan = 0, t_absorb = 0, t_out = 0, tt;
-    int n_cols = 0, n_chunks = 0, n_iter = 0, n_absorb = 0, last_R = 0, n_acc = 0;
+    int n_cols = 0, n_chunks = 0, n_iter = 0, n_absorb = 0, last_R = 0, n_acc = 0, n_fail = 0;
 #define PROF_T0 tt = clock64();
 #define PROF_ADD(x) x += clock64() - tt;
 #else
@@ -124,6 +140,19 @@ k_query_tile_sorted(QueryArgs a)
     for (int i = 0; i < KC; ++i) best[i] = (i < KC - cap) ? 0ull : kEmptyKey;
 #pragma unroll
     for (int i = 0; i < kPend; ++i) pend_lds[kPendHalf + i * kQueryBlock] = (uint32_t)(kEmptyKey >> 32);   // all pending slots empty
+    if constexpr (FLAT) {
+        float w[NV * 4];
+#pragma unroll
+        for (int c = 0; c < NV * 4; ++c) w[c] = 0.0f;
+#pragma unroll
+        for (int c = 0; c < D; ++c) w[c] = s.x[c];
+        w[D] = __uint_as_float((uint32_t)(kEmptyKey >> 32));
+#pragma unroll
+        for (int v = 0; v < NV; ++v) qx[lane * NV + v] = make_float4(w[4 * v], w[4 * v + 1], w[4 * v + 2], w[4 * v + 3]);
+        pend_cnt[lane] = 0;
+        fl_start[kQueryBlock] = 0x7fffffff;
+        if (LOWER) qlower[lane] = lower;
+    }
     int32_t cand = 0;
     int32_t useful = 0;   // candidates this lane evaluated
     int32_t passes = 0;   // scan passes of the wave (kUnroll lane slots each)
@@ -131,7 +160,8 @@ k_query_tile_sorted(QueryArgs a)
     auto absorb = [&]() {
         uint64_t pend[kPend];
 #ifdef FG_TILE_PROF
-        const int32_t cnt = (int32_t)((pend_top - pend_base) / (kQueryBlock * 4));
+        const int32_t cnt = FLAT ? (int32_t)(pend_cnt[lane] < kPend ? pend_cnt[lane] : kPend)
+                                 : (int32_t)((pend_top - pend_base) / (kQueryBlock * 4));
 #endif
         // unused slots hold the empty key's distance word (refilled below), whatever their index word: such keys
         // lie at or above the empty key and sort behind every real one
@@ -147,6 +177,11 @@ k_query_tile_sorted(QueryArgs a)
 #endif
         pend_top = pend_base;
         s.tau = best[KC - 1];
+        if constexpr (FLAT) {
+            pend_cnt[lane] = 0;
+            reinterpret_cast<uint32_t*>(qx + lane * NV)[D] = (uint32_t)(s.tau >> 32);
+            __syncthreads();
+        }
     };
 
     int32_t R = 0;
@@ -234,8 +269,8 @@ k_query_tile_sorted(QueryArgs a)
             if (b2 > a2) { lo = a2 < lo ? a2 : lo; hi = b2 > hi ? b2 : hi; }
             const int32_t PA = wave_min_i32(lo), PB = wave_max_i32(hi);
             PROF_ADD(t_setup)
-            for (int32_t base = PA; base < PB; base += kStageChunk) {
-                const int32_t cnt_pts = PB - base < kStageChunk ? PB - base : kStageChunk;
+            for (int32_t base = PA; base < PB; base += CHUNK) {
+                const int32_t cnt_pts = PB - base < CHUNK ? PB - base : CHUNK;
                 PROF_T0
 #ifdef FG_TILE_PROF
                 ++n_chunks;
@@ -259,6 +294,7 @@ k_query_tile_sorted(QueryArgs a)
                 __syncthreads();
                 PROF_ADD(t_stage)
                 PROF_T0
+                if constexpr (!FLAT) {
                 // this lane's two sub-ranges clipped to the chunk, walked one after the other
                 const int32_t top = base + cnt_pts;
                 int32_t q = a1 > base ? a1 : base, e = b1 < top ? b1 : top;
@@ -311,11 +347,140 @@ k_query_tile_sorted(QueryArgs a)
                     if (__any(pend_top > pend_full)) absorb();
 #endif
                 }
+                } else {
+                // Flattened scan: the work of this chunk is dealt out evenly over the lanes, whichever query it belongs
+                // to.  Every query's clipped run is cut into passes of kUnroll candidates; the passes of all queries
+                // are put in one order (prefix sum over the lanes) and lane L takes passes [L*C, (L+1)*C) of it.  What
+                // a lane keeps goes to the pending buffer of the query the pass belongs to (slots from a counter in
+                // LDS), and that query's lane merges it as before.
+                const int32_t top = base + cnt_pts;
+                const int32_t q = a1 > base ? a1 : base, e = b1 < top ? b1 : top;
+                const int32_t q2 = a2 > base ? a2 : base, e2 = b2 < top ? b2 : top;
+                const int32_t len1 = e > q ? e - q : 0, len2 = e2 > q2 ? e2 - q2 : 0;
+                useful += len1 + len2;
+                if (COUNT) cand += len1 + len2;
+                const bool second_runs = __any(len2 > 0);      // only the centre column (and shell 0) has two runs per lane
+                for (int run = 0; run < 2; ++run) {
+                    if (run == 1 && !second_runs) break;
+                    const int32_t len = run ? len2 : len1;
+                    const uint64_t m = __ballot(len > 0);
+                    if (m == 0) continue;
+                    const int32_t nq = __popcll(m);
+                    const int32_t ng = (len + kUnroll - 1) / kUnroll;          // passes this run takes
+                    const int32_t incl = wave_incl_scan_dpp_i32(ng);
+                    const int32_t TG = __builtin_amdgcn_readlane(incl, kQueryBlock - 1);
+                    __syncthreads();
+                    if (len > 0) {
+                        const int32_t rank = __popcll(m & lt_mask);
+                        fl_start[rank] = incl - ng;
+                        static_assert(CHUNK <= 512, "run start and length are packed in 10 bits each");
+                        fl_info[rank] = ((run ? q2 : q) - base) | (len << 10) | (lane << 20);
+                    }
+                    if (lane >= nq) fl_start[lane] = 0x7fffffff;
+                    __syncthreads();
+                    const int32_t C = (TG + kQueryBlock - 1) / kQueryBlock;
+                    int32_t f = lane * C;
+                    const int32_t f_end = f + C < TG ? f + C : TG;
+                    int32_t j = 0;
+#pragma unroll
+                    for (int step = 32; step > 0; step >>= 1)
+                        if (fl_start[j + step] <= f) j += step;
+                    int32_t run_end = f, pos = 0, left = 0, owner = lane;
+                    float xq[NV * 4];
+                    auto load_run = [&]() {
+                        const int32_t info = fl_info[j];
+                        const int32_t first = fl_start[j], nxt_start = fl_start[j + 1];
+                        owner = info >> 20;
+                        pos = (info & 0x3ff) + (f - first) * kUnroll;
+                        left = ((info >> 10) & 0x3ff) - (f - first) * kUnroll;
+                        run_end = nxt_start < f_end ? nxt_start : f_end;
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) {
+                            const float4 g = qx[owner * NV + v];
+                            xq[4 * v] = g.x; xq[4 * v + 1] = g.y; xq[4 * v + 2] = g.z; xq[4 * v + 3] = g.w;
+                        }
+                    };
+#pragma unroll
+                    for (int c = 0; c < NV * 4; ++c) xq[c] = 0.0f;
+                    if (f < f_end) load_run();
+                    for (;;) {
+                        const bool busy = f < run_end;
+                        if (!__any(busy)) break;
+                        const int32_t rem = busy ? left : 0;
+                        float w[kUnroll][NV * 4];
+                        const uint32_t tau_hi = __float_as_uint(xq[D]);
+                        const int32_t i0 = busy ? pos : 0;          // reads past the run stay inside the padded chunk
+#pragma unroll
+                        for (int u = 0; u < kUnroll; ++u) {
+#pragma unroll
+                            for (int v = 0; v < NV; ++v) {
+                                const float4 g = stage[(i0 + u) * NV + v];
+                                w[u][4 * v] = g.x; w[u][4 * v + 1] = g.y; w[u][4 * v + 2] = g.z; w[u][4 * v + 3] = g.w;
+                            }
+                        }
+                        uint32_t bits[kUnroll];
+                        bool acc[kUnroll];
+                        int32_t na = 0;
+                        uint64_t low = 0;
+                        if (LOWER) low = qlower[owner];
+#pragma unroll
+                        for (int u = 0; u < kUnroll; ++u) {
+                            float diff = xq[0] - w[u][0];
+                            float d2 = diff * diff;
+#pragma unroll
+                            for (int c = 1; c < D; ++c) {
+                                diff = xq[c] - w[u][c];
+                                d2 = d2 + diff * diff;
+                            }
+                            bits[u] = __float_as_uint(d2);
+                            // kept if its distance does not exceed the k-th best's (a tie on the distance may lose on
+                            // the index: the merge decides); NaN (poisoned) patterns lie above every bound
+                            acc[u] = u < rem && bits[u] <= tau_hi &&
+                                     (!LOWER || (((uint64_t)bits[u] << 32) | __float_as_uint(w[u][D])) > low);
+                            na += acc[u] ? 1 : 0;
+                        }
+                        bool fail = false, hot = false;
+                        if (na > 0) {
+                            const int32_t s0 = (int32_t)atomicAdd(&pend_cnt[owner], (uint32_t)na);
+                            fail = s0 + na > kPend;                 // no room: nothing is stored, the pass is repeated
+                            hot = s0 + na > kPend - kUnroll;        // the next pass might not fit
+                            if (!fail) {
+                                static_assert(kPendHalf * 4 == 16 * 256 && kQueryBlock * 4 == 0x100, "offsets below");
+                                uint32_t wptr = (pend_base - (uint32_t)lane * 4u) + (uint32_t)owner * 4u + (uint32_t)s0 * (kQueryBlock * 4u);
+#pragma unroll
+                                for (int u = 0; u < kUnroll; ++u) {
+                                    if (acc[u]) {
+                                        asm volatile("ds_write2st64_b32 %0, %1, %2 offset1:16\n\tv_add_u32 %0, 0x100, %0"
+                                                     : "+v"(wptr) : "v"(__float_as_uint(w[u][D])), "v"(bits[u]) : "memory");
+                                    }
+                                }
+                            }
+                        }
+                        if (busy && !fail) { ++f; pos += kUnroll; left -= kUnroll; }
+                        ++passes;
+                        const bool merge = __any(hot);
+#ifdef FG_TILE_PROF
+                        ++n_iter;
+                        if (__any(fail)) ++n_fail;
+                        if (merge) { long long t2 = clock64(); __syncthreads(); absorb(); t_absorb += clock64() - t2; ++n_absorb; }
+#else
+                        if (merge) { __syncthreads(); absorb(); }
+#endif
+                        if (f >= run_end && f < f_end) { ++j; load_run(); }
+                        else if (merge) xq[D] = reinterpret_cast<const float*>(qx + owner * NV)[D];
+                    }
+                }
+                }
                 PROF_ADD(t_scan)
             }
         }
         PROF_T0
-        if (__any(pend_top != pend_base)) absorb();
+        if constexpr (FLAT) {
+            __syncthreads();
+            if (__any(pend_cnt[lane] != 0)) absorb();
+        } else {
+            if (__any(pend_top != pend_base)) absorb();
+        }
         PROF_ADD(t_absorb)
         if (active && s.certified(R)) active = false;
         const int32_t n_active = __popcll(__ballot(active));
@@ -427,15 +592,46 @@ k_query_tile_sorted(QueryArgs a)
         pr[18] = (int32_t)__builtin_amdgcn_s_getreg(63492);    // HW_ID
         pr[19] = (int32_t)__builtin_amdgcn_s_getreg(63508);    // XCC_ID
         pr[20] = (int32_t)blockIdx.x;
+        pr[21] = n_fail;
     }
 #endif
+}
+
+// Which list sizes have the flattened scan compiled in: those whose direct scan keeps its register allocation next
+// to it (at 16 and 48 keys, four and three wavefronts per SIMD, the joint kernel spilled 60-100 registers).
+template <int KC> constexpr bool tile_has_flat() { return KC == 32 || KC == 64; }
+
+// The kernel: one workgroup of one wavefront per tile.  Tiles the ordering kernels marked as uneven take the
+// flattened scan, all others, and every tile of an unordered launch, the direct one.  One kernel with a branch,
+// not two kernels: a tile alone takes ~0.1 ms from its first shell to its last row whatever runs beside it, so a
+// second kernel for the uneven tiles adds its whole tail.  a.algo == 2 sends every tile to the flattened scan
+// (tests).  The counting instantiation scans directly.
+template <int D, int DB, int KC, bool COUNT, bool LOWER>
+__global__ void __launch_bounds__(kQueryBlock) __attribute__((amdgpu_waves_per_eu(tile_waves<KC, D>(), tile_waves<KC, D>())))
+k_query_tile_sorted(QueryArgs a)
+{
+    extern __shared__ uint64_t lds64[];
+    // an entry of the order: the tile, heaviest first, and above it the flag of an uneven tile
+    const int32_t entry = a.tile_order ? a.tile_order[blockIdx.x] : (int32_t)blockIdx.x;
+    const int32_t tile = entry & ((1 << kOrderFlagBit) - 1);
+    if constexpr (tile_has_flat<KC>() && !COUNT) {
+        const bool uneven = a.algo == 2 || ((entry >> kOrderFlagBit) & 1);
+        if (uneven) {
+            tile_body<D, DB, KC, COUNT, LOWER, true>(a, tile, lds64);
+            return;
+        }
+    }
+    tile_body<D, DB, KC, COUNT, LOWER, false>(a, tile, lds64);
 }
 
 template <int KC, int D>
 constexpr size_t tile_sorted_lds_bytes()
 {
-    const size_t scan = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (kStageChunk + kUnroll);
+    const size_t flat = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (kFlatChunk + kUnroll + kQueryBlock) +
+                        (size_t)kQueryBlock * 4 * 3 + 8 + (size_t)kQueryBlock * 8;
+    const size_t direct = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (kStageChunk + kUnroll);
     const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kDumpStride * 4;
+    const size_t scan = (tile_has_flat<KC>() && flat > direct) ? flat : direct;
     return scan > out ? scan : out;
 }
 

@@ -217,6 +217,68 @@ def test_tile_and_list_kernels_both_run_and_agree_with_the_plain_walk():
         assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "plain walk nb=%d" % nb)
 
 
+@pytest.mark.parametrize("d,k", [(2, 20), (3, 32), (3, 64), (4, 33), (5, 25), (8, 64), (10, 20), (3, 100), (3, 128)])
+def test_flattened_scan_on_every_tile(d, k):
+    """query_algo = 2: the tile kernel's flattened scan (the work of a chunk dealt out evenly over the lanes,
+    kept candidates appended to their query's pending buffer from any lane) on every tile, for the list sizes
+    that have it (17..32 and 49..64 keys; K = 100 and 128 reach it in their first pass, 128 in both).  Clustered
+    points with duplicates, a short and an empty split, direction flags."""
+    rng = np.random.Generator(np.random.PCG64(500 + 10 * d + k))
+    sizes = [2300, 5, 0, 1700]
+    n = sum(sizes)
+    x, rs = W.uniform(n, d, seed=510 + d + k, sizes=sizes)
+    x[100:400] = x[100]                                   # 300 copies of one point: ties on distance 0
+    x[2400:3400] = x[2400] + 0.01 * (x[2400:3400] - 0.5)  # a dense cluster next to sparse points: uneven tiles
+    x = np.ascontiguousarray(x)
+    xt, rt = torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV)
+    oi, od = oracle.knn(x, rs, k)
+    for nb in (0, 7):
+        bn = B.fg_bin_points(xt, rt, k, nb, min(d, 3) if nb else 0)
+        bn.raw.query_algo = 2
+        gi, gd = B.fg_query_binned(bn, rt, k)
+        torch.cuda.synchronize()
+        assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "flattened d=%d k=%d nb=%d" % (d, k, nb))
+    direction = rng.integers(0, 4, size=n).astype(np.int32)
+    oi, od = oracle.knn(x, rs, k, direction=direction)
+    bn = B.fg_bin_points(xt, rt, k)
+    dt = torch.from_numpy(direction).to(DEV)
+    bn.raw.dir = dt.data_ptr()
+    bn.raw.query_algo = 2
+    gi, gd = B.fg_query_binned(bn, rt, k)
+    torch.cuda.synchronize()
+    assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "flattened with flags d=%d k=%d" % (d, k))
+
+
+def test_uneven_tiles_take_the_flattened_scan_in_an_ordered_launch():
+    """More than 1024 tiles: the ordering kernels rank the tiles and mark the uneven ones; on clustered points
+    some tiles must be marked (and scanned flattened), on a regular lattice none."""
+    rng = np.random.Generator(np.random.PCG64(77))
+    n, k = 90_000, 32
+    centres = rng.random((40, 3)) * 10.0
+    x = centres[rng.integers(0, 40, size=n)] + rng.standard_normal((n, 3)) * np.exp(rng.uniform(np.log(0.01), np.log(0.5), size=(n, 1)))
+    x[:9000] = rng.random((9000, 3)) * 10.0
+    x = np.ascontiguousarray(x.astype(np.float32))
+    rs = np.array([0, 50_000, n], dtype=np.int32)
+    xt, rt = torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV)
+    bn = B.fg_bin_points(xt, rt, k)
+    gi, gd = B.fg_query_binned(bn, rt, k)
+    torch.cuda.synchronize()
+    n_tiles = (n + 63) // 64
+    order = bn._view(bn.raw.tile_order, 2 * n_tiles + 128, torch.int32).cpu().numpy()
+    tiles, flags = order[:n_tiles] & ((1 << 30) - 1), order[:n_tiles] >> 30
+    assert np.array_equal(np.sort(tiles), np.arange(n_tiles))               # a permutation of the tiles
+    assert 0 < flags.sum() < n_tiles
+    assert np.array_equal(flags, (order[n_tiles:2 * n_tiles][tiles] >> 6) & 1)
+    rows = np.sort(rng.choice(n, size=3000, replace=False)).astype(np.int64)
+    oi, od = oracle.knn_rows(x, rs, k, rows)
+    gi, gd = gi.cpu().numpy(), gd.cpu().numpy()
+    assert np.array_equal(gi[rows], oi) and np.array_equal(gd[rows].view(np.uint32), od.view(np.uint32))
+    bn.raw.query_algo = 1                                                    # the plain walk agrees on every row
+    gi1, gd1 = B.fg_query_binned(bn, rt, k)
+    torch.cuda.synchronize()
+    assert np.array_equal(gi1.cpu().numpy(), gi) and np.array_equal(gd1.cpu().numpy().view(np.uint32), gd.view(np.uint32))
+
+
 def gpu_knn_dir(x, rs, direction, k, n_bins=0, d_bin=0):
     idx, d2 = B.fg_binned_select_knn_dir(torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV),
                                          torch.from_numpy(direction).to(DEV), k, n_bins, d_bin)
