@@ -90,7 +90,7 @@ typedef struct {
     int32_t query_algo;        /* 0 (set by fg_bin_points): tile kernel + list kernel; 1: the one-lane-per-query
                                   shell walk for every query (slower; same result; kept for cross-checking);
                                   2: as 0, with the tile kernel's flattened scan for every tile instead of the
-                                  uneven ones only, where the list size has it (same result; for tests) */
+                                  uneven ones only (same result; for tests) */
     int32_t defer_lanes;       /* tuning knob of the tile kernel, 0..64 (set by fg_bin_points): after shell 1 a
                                   wavefront goes on to the next shell only while more than this many of its 64
                                   queries are unfinished (and its lanes have been evenly loaded so far); the

@@ -597,10 +597,6 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
 #endif
 }
 
-// Which list sizes have the flattened scan compiled in: those whose direct scan keeps its register allocation next
-// to it (at 16 and 48 keys, four and three wavefronts per SIMD, the joint kernel spilled 60-100 registers).
-template <int KC> constexpr bool tile_has_flat() { return KC == 32 || KC == 64; }
-
 // The kernel: one workgroup of one wavefront per tile.  Tiles the ordering kernels marked as uneven take the
 // flattened scan, all others, and every tile of an unordered launch, the direct one.  One kernel with a branch,
 // not two kernels: a tile alone takes ~0.1 ms from its first shell to its last row whatever runs beside it, so a
@@ -614,7 +610,7 @@ k_query_tile_sorted(QueryArgs a)
     // an entry of the order: the tile, heaviest first, and above it the flag of an uneven tile
     const int32_t entry = a.tile_order ? a.tile_order[blockIdx.x] : (int32_t)blockIdx.x;
     const int32_t tile = entry & ((1 << kOrderFlagBit) - 1);
-    if constexpr (tile_has_flat<KC>() && !COUNT) {
+    if constexpr (!COUNT) {
         const bool uneven = a.algo == 2 || ((entry >> kOrderFlagBit) & 1);
         if (uneven) {
             tile_body<D, DB, KC, COUNT, LOWER, true>(a, tile, lds64);
@@ -631,7 +627,7 @@ constexpr size_t tile_sorted_lds_bytes()
                         (size_t)kQueryBlock * 4 * 3 + 8 + (size_t)kQueryBlock * 8;
     const size_t direct = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (kStageChunk + kUnroll);
     const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kDumpStride * 4;
-    const size_t scan = (tile_has_flat<KC>() && flat > direct) ? flat : direct;
+    const size_t scan = flat > direct ? flat : direct;
     return scan > out ? scan : out;
 }
 

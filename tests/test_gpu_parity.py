@@ -217,12 +217,13 @@ def test_tile_and_list_kernels_both_run_and_agree_with_the_plain_walk():
         assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "plain walk nb=%d" % nb)
 
 
-@pytest.mark.parametrize("d,k", [(2, 20), (3, 32), (3, 64), (4, 33), (5, 25), (8, 64), (10, 20), (3, 100), (3, 128)])
+@pytest.mark.parametrize("d,k", [(2, 20), (3, 9), (3, 16), (3, 32), (3, 40), (3, 64), (4, 33), (5, 25), (6, 48), (8, 64), (10, 20),
+                                 (3, 100), (3, 128)])
 def test_flattened_scan_on_every_tile(d, k):
     """query_algo = 2: the tile kernel's flattened scan (the work of a chunk dealt out evenly over the lanes,
-    kept candidates appended to their query's pending buffer from any lane) on every tile, for the list sizes
-    that have it (17..32 and 49..64 keys; K = 100 and 128 reach it in their first pass, 128 in both).  Clustered
-    points with duplicates, a short and an empty split, direction flags."""
+    kept candidates appended to their query's pending buffer from any lane) on every tile, for every list size
+    and both passes of a long list.  Clustered points with duplicates, a short and an empty split, direction
+    flags."""
     rng = np.random.Generator(np.random.PCG64(500 + 10 * d + k))
     sizes = [2300, 5, 0, 1700]
     n = sum(sizes)
