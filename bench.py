@@ -118,11 +118,11 @@ def main() -> int:
     ms_bin = timed(lambda: B.fg_bin_points(x, rs, k, args.n_bins, args.d_bin, ws), reps)
     binning = B.fg_bin_points(x, rs, k, args.n_bins, args.d_bin, ws)
     ms_query = timed(lambda: B.fg_query_binned(binning, rs, k, out_idx, out_d2), reps)
+    deferred = int(binning.work_count.item())                     # of the timed query launches
     cand = torch.empty((n,), dtype=torch.int32, device=dev)
     B.fg_query_binned(binning, rs, k, out_idx, out_d2, cand)      # counting instantiation, never timed
     torch.cuda.synchronize()
     total_cand = int(cand.to(torch.int64).sum().item())
-    deferred = int(binning.work_count.item())
     ms_bwd = timed(lambda: B.fg_knn_backward_binned(binning, g, out_idx, x, grad), reps) if w.backward else None
     # the stand-alone backward bins once more, into the same workspace: `binning` is dead from here on
     ms_bwd_alone = timed(lambda: B.fg_knn_backward(g, out_idx, x, rs, grad, ws), reps) if w.backward else None
