@@ -610,7 +610,12 @@ k_query_tile_sorted(QueryArgs a)
     // an entry of the order: the tile, heaviest first, and above it the flag of an uneven tile
     const int32_t entry = a.tile_order ? a.tile_order[blockIdx.x] : (int32_t)blockIdx.x;
     const int32_t tile = entry & ((1 << kOrderFlagBit) - 1);
-    if constexpr (!COUNT) {
+#ifdef FG_TILE_PROF
+    constexpr bool kProfiled = true;     // the instrumented build reports through the counting instantiation
+#else
+    constexpr bool kProfiled = false;
+#endif
+    if constexpr (!COUNT || kProfiled) {
         const bool uneven = a.algo == 2 || ((entry >> kOrderFlagBit) & 1);
         if (uneven) {
             tile_body<D, DB, KC, COUNT, LOWER, true>(a, tile, lds64);
