@@ -75,18 +75,23 @@ __device__ __forceinline__ void store_row_from_registers(const uint64_t (&best)[
 
 constexpr int kTileFlatBit = 6;   // in a tile's class word: the ordering kernels found the tile uneven
 constexpr int kOrderFlagBit = 30;  // the same flag in the tile's entry of the order (tiles number below 2^25)
-#ifndef FG_FLAT_CHUNK
-#define FG_FLAT_CHUNK 96
-#endif
-// Points staged per chunk by the flattened scan: its extra LDS comes out of the stage, so that a workgroup needs
-// no more than the direct scan's and three wavefronts per SIMD still fit a CU's 160 KB (with 160 points, 0.8 KB more
-// per workgroup, every tile ran at 11 wavefronts per CU instead of 12: +7 % on even data).
-constexpr int kFlatChunk = FG_FLAT_CHUNK;
+// Points staged per chunk by the flattened scan: its extra LDS (the queries' coordinates, counters, run tables) comes
+// out of the stage, so that a workgroup needs no more than the direct scan's and three wavefronts per SIMD still
+// fit a CU's 160 KB (with 0.8 KB more per workgroup every tile ran at 11 wavefronts per CU instead of 12: +7 %
+// on even data).  The largest multiple of 16 that fits, at least 96: d = 3: 96, d = 4..7: 144, d = 8..10: 160.
+constexpr size_t kFlatTables = (size_t)kQueryBlock * 4 * 3 + 8 + (size_t)kQueryBlock * 8;   // counters, runs, starts, lower bounds
+template <int D> constexpr int flat_chunk()
+{
+    const int nv = stage_vecs<D>();
+    const int room = (int)(((size_t)nv * 16 * (kStageChunk + kUnroll) - kFlatTables) / ((size_t)nv * 16)) - kUnroll - kQueryBlock;
+    const int chunk = room / 16 * 16;
+    return chunk < 96 ? 96 : chunk;
+}
 
 template <int D, int DB, int KC, bool COUNT, bool LOWER, bool FLAT>
 __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile, uint64_t* lds64)
 {
-    constexpr int CHUNK = FLAT ? kFlatChunk : kStageChunk;
+    constexpr int CHUNK = FLAT ? flat_chunk<D>() : kStageChunk;
     // LDS: [pending kPend x 64 keys][stage (D+1) x kStageChunk words]; re-used at the end as
     //      [rows 64 words][KC x 64 words of the sorted lists, indices first, distances second]
     const int lane = threadIdx.x;
@@ -628,8 +633,7 @@ k_query_tile_sorted(QueryArgs a)
 template <int KC, int D>
 constexpr size_t tile_sorted_lds_bytes()
 {
-    const size_t flat = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (kFlatChunk + kUnroll + kQueryBlock) +
-                        (size_t)kQueryBlock * 4 * 3 + 8 + (size_t)kQueryBlock * 8;
+    const size_t flat = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (flat_chunk<D>() + kUnroll + kQueryBlock) + kFlatTables;
     const size_t direct = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (kStageChunk + kUnroll);
     const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kDumpStride * 4;
     const size_t scan = flat > direct ? flat : direct;
