@@ -88,10 +88,17 @@ template <int D> constexpr int flat_chunk()
     return chunk < 96 ? 96 : chunk;
 }
 
+// Lists of up to 16 keys leave registers for four wavefronts per SIMD, but 16 workgroups of 12 KB do not fit a CU's
+// 160 KB of LDS (13 did): with single-vector points (d <= 3) the direct scan stages 112 points per chunk
+// instead of 256 and a workgroup stays under 10 KB (1M uniform points, d = 3: K = 16 0.31 -> 0.27 ms, K = 10
+// 0.31 -> 0.27 ms).  The flattened scan's tables do not fit that budget: these kernels scan every tile directly.
+template <int KC, int D> constexpr bool tile_small_lds() { return KC <= 16 && stage_vecs<D>() == 1; }
+template <int KC, int D> constexpr int direct_chunk() { return tile_small_lds<KC, D>() ? 112 : kStageChunk; }
+
 template <int D, int DB, int KC, bool COUNT, bool LOWER, bool FLAT>
 __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile, uint64_t* lds64)
 {
-    constexpr int CHUNK = FLAT ? flat_chunk<D>() : kStageChunk;
+    constexpr int CHUNK = FLAT ? flat_chunk<D>() : direct_chunk<KC, D>();
     // LDS: [pending kPend x 64 keys][stage (D+1) x kStageChunk words]; re-used at the end as
     //      [rows 64 words][KC x 64 words of the sorted lists, indices first, distances second]
     const int lane = threadIdx.x;
@@ -620,7 +627,7 @@ k_query_tile_sorted(QueryArgs a)
 #else
     constexpr bool kProfiled = false;
 #endif
-    if constexpr (!COUNT || kProfiled) {
+    if constexpr ((!COUNT || kProfiled) && !tile_small_lds<KC, D>()) {
         const bool uneven = a.algo == 2 || ((entry >> kOrderFlagBit) & 1);
         if (uneven) {
             tile_body<D, DB, KC, COUNT, LOWER, true>(a, tile, lds64);
@@ -634,9 +641,9 @@ template <int KC, int D>
 constexpr size_t tile_sorted_lds_bytes()
 {
     const size_t flat = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (flat_chunk<D>() + kUnroll + kQueryBlock) + kFlatTables;
-    const size_t direct = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (kStageChunk + kUnroll);
+    const size_t direct = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (direct_chunk<KC, D>() + kUnroll);
     const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kDumpStride * 4;
-    const size_t scan = flat > direct ? flat : direct;
+    const size_t scan = (flat > direct && !tile_small_lds<KC, D>()) ? flat : direct;
     return scan > out ? scan : out;
 }
 
