@@ -75,30 +75,39 @@ __device__ __forceinline__ void store_row_from_registers(const uint64_t (&best)[
 
 constexpr int kTileFlatBit = 6;   // in a tile's class word: the ordering kernels found the tile uneven
 constexpr int kOrderFlagBit = 30;  // the same flag in the tile's entry of the order (tiles number below 2^25)
-// Points staged per chunk by the flattened scan: its extra LDS (the queries' coordinates, counters, run tables) comes
-// out of the stage, so that a workgroup needs no more than the direct scan's and three wavefronts per SIMD still
-// fit a CU's 160 KB (with 0.8 KB more per workgroup every tile ran at 11 wavefronts per CU instead of 12: +7 %
-// on even data).  The largest multiple of 16 that fits, at least 96: d = 3: 96, d = 4..7: 144, d = 8..10: 160.
+// LDS of a workgroup (one wavefront): the pending buffers (8 KB), the stage, and for the flattened scan its tables.
+// How many wavefronts a CU holds is set by the registers (tile_waves) only if 4 * tile_waves workgroups fit its
+// 160 KB of LDS, so the stage is sized for that: 16 workgroups (lists of 16 keys) get 10 KB each, 12 get 12.5 KB
+// (measured: 12.6 KB still gives 12, 13.1 KB gives 11), 8 get 20 KB.  With a fixed 256-point stage d >= 4 ran at
+// 9 and d >= 8 at 7 wavefronts per CU instead of 12, and 16-key lists at 13 instead of 16: 1M uniform points,
+// K = 32: d = 4 1.17 -> 0.95 ms, d = 5 2.80 -> 2.31 ms, d = 8 51 -> 41 ms; d = 3, K = 16: 0.31 -> 0.27 ms.
+constexpr size_t kPendBytes = (size_t)kPend * kQueryBlock * 8;
 constexpr size_t kFlatTables = (size_t)kQueryBlock * 4 * 3 + 8 + (size_t)kQueryBlock * 8;   // counters, runs, starts, lower bounds
-template <int D> constexpr int flat_chunk()
+template <int KC, int D> constexpr size_t tile_lds_budget()
 {
-    const int nv = stage_vecs<D>();
-    const int room = (int)(((size_t)nv * 16 * (kStageChunk + kUnroll) - kFlatTables) / ((size_t)nv * 16)) - kUnroll - kQueryBlock;
-    const int chunk = room / 16 * 16;
-    return chunk < 96 ? 96 : chunk;
+    return tile_waves<KC, D>() >= 4 ? 10240 : (tile_waves<KC, D>() == 3 ? 12800 : 20480);
 }
-
-// Lists of up to 16 keys leave registers for four wavefronts per SIMD, but 16 workgroups of 12 KB do not fit a CU's
-// 160 KB of LDS (13 did): with single-vector points (d <= 3) the direct scan stages 112 points per chunk
-// instead of 256 and a workgroup stays under 10 KB (1M uniform points, d = 3: K = 16 0.31 -> 0.27 ms, K = 10
-// 0.31 -> 0.27 ms).  The flattened scan's tables do not fit that budget: these kernels scan every tile directly.
-template <int KC, int D> constexpr bool tile_small_lds() { return KC <= 16 && stage_vecs<D>() == 1; }
-template <int KC, int D> constexpr int direct_chunk() { return tile_small_lds<KC, D>() ? 112 : kStageChunk; }
+constexpr int chunk_that_fits(size_t bytes, int nv)    // points: a multiple of 16 in [64, 256], kUnroll more are padding
+{
+    const int room = (int)(bytes / ((size_t)nv * 16)) - kUnroll;
+    const int chunk = room / 16 * 16;
+    return chunk > kStageChunk ? kStageChunk : (chunk < 64 ? 64 : chunk);
+}
+template <int KC, int D> constexpr int direct_chunk() { return chunk_that_fits(tile_lds_budget<KC, D>() - kPendBytes, stage_vecs<D>()); }
+// the flattened scan is compiled in where its tables leave room for a stage of at least 64 points
+template <int KC, int D> constexpr bool tile_has_flat()
+{
+    return tile_lds_budget<KC, D>() >= kPendBytes + kFlatTables + (size_t)stage_vecs<D>() * 16 * (64 + kUnroll);
+}
+template <int KC, int D> constexpr int flat_chunk()
+{
+    return tile_has_flat<KC, D>() ? chunk_that_fits(tile_lds_budget<KC, D>() - kPendBytes - kFlatTables, stage_vecs<D>()) : 64;
+}
 
 template <int D, int DB, int KC, bool COUNT, bool LOWER, bool FLAT>
 __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile, uint64_t* lds64)
 {
-    constexpr int CHUNK = FLAT ? flat_chunk<D>() : direct_chunk<KC, D>();
+    constexpr int CHUNK = FLAT ? flat_chunk<KC, D>() : direct_chunk<KC, D>();
     // LDS: [pending kPend x 64 keys][stage (D+1) x kStageChunk words]; re-used at the end as
     //      [rows 64 words][KC x 64 words of the sorted lists, indices first, distances second]
     const int lane = threadIdx.x;
@@ -112,10 +121,9 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
     uint32_t pend_top = pend_base;
     constexpr int NV = stage_vecs<D>();
     float4* stage = reinterpret_cast<float4*>(lds64 + kPend * kQueryBlock);   // [kStageChunk][NV]
-    // flattened scan only: after the stage, [64][NV] the queries (coordinates, then the distance word of the k-th
-    // best), [64] pending counts, [64] run descriptors, [66] run starts in the flattened order, [64] lower bounds
-    float4* const qx = stage + (CHUNK + kUnroll) * NV;
-    uint32_t* const pend_cnt = reinterpret_cast<uint32_t*>(qx + kQueryBlock * NV);
+    // flattened scan only: after the stage, [64] pending counts, [64] run descriptors, [66] run starts in the
+    // flattened order, [64] lower bounds
+    uint32_t* const pend_cnt = reinterpret_cast<uint32_t*>(stage + (CHUNK + kUnroll) * NV);
     int32_t* const fl_info = reinterpret_cast<int32_t*>(pend_cnt + kQueryBlock);
     int32_t* const fl_start = fl_info + kQueryBlock;
     uint64_t* const qlower = reinterpret_cast<uint64_t*>(fl_start + kQueryBlock + 2);
@@ -153,14 +161,6 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
 #pragma unroll
     for (int i = 0; i < kPend; ++i) pend_lds[kPendHalf + i * kQueryBlock] = (uint32_t)(kEmptyKey >> 32);   // all pending slots empty
     if constexpr (FLAT) {
-        float w[NV * 4];
-#pragma unroll
-        for (int c = 0; c < NV * 4; ++c) w[c] = 0.0f;
-#pragma unroll
-        for (int c = 0; c < D; ++c) w[c] = s.x[c];
-        w[D] = __uint_as_float((uint32_t)(kEmptyKey >> 32));
-#pragma unroll
-        for (int v = 0; v < NV; ++v) qx[lane * NV + v] = make_float4(w[4 * v], w[4 * v + 1], w[4 * v + 2], w[4 * v + 3]);
         pend_cnt[lane] = 0;
         fl_start[kQueryBlock] = 0x7fffffff;
         if (LOWER) qlower[lane] = lower;
@@ -191,7 +191,6 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
         s.tau = best[KC - 1];
         if constexpr (FLAT) {
             pend_cnt[lane] = 0;
-            reinterpret_cast<uint32_t*>(qx + lane * NV)[D] = (uint32_t)(s.tau >> 32);
             __syncthreads();
         }
     };
@@ -398,29 +397,38 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
                     for (int step = 32; step > 0; step >>= 1)
                         if (fl_start[j + step] <= f) j += step;
                     int32_t run_end = f, pos = 0, left = 0, owner = lane;
-                    float xq[NV * 4];
-                    auto load_run = [&]() {
+                    float xq[D];
+                    uint32_t tau_hi = 0;
+                    // The lane's place in run j: where the run's candidates sit in the stage, how many are left, and
+                    // the query it belongs to, whose coordinates and k-th best are read from that query's lane
+                    // (cross-lane reads return nothing from a lane that is switched off: every lane executes this,
+                    // lanes without work with a harmless run number, and `take` says who keeps the result).
+                    auto load_run = [&](bool take) {
                         const int32_t info = fl_info[j];
                         const int32_t first = fl_start[j], nxt_start = fl_start[j + 1];
-                        owner = info >> 20;
-                        pos = (info & 0x3ff) + (f - first) * kUnroll;
-                        left = ((info >> 10) & 0x3ff) - (f - first) * kUnroll;
-                        run_end = nxt_start < f_end ? nxt_start : f_end;
+                        const int32_t from = info >> 20;
+                        float xo[D];
 #pragma unroll
-                        for (int v = 0; v < NV; ++v) {
-                            const float4 g = qx[owner * NV + v];
-                            xq[4 * v] = g.x; xq[4 * v + 1] = g.y; xq[4 * v + 2] = g.z; xq[4 * v + 3] = g.w;
+                        for (int c = 0; c < D; ++c) xo[c] = __shfl(s.x[c], from, 64);
+                        const uint32_t to = (uint32_t)__shfl((int)(uint32_t)(s.tau >> 32), from, 64);
+                        if (take) {
+                            owner = from;
+                            pos = (info & 0x3ff) + (f - first) * kUnroll;
+                            left = ((info >> 10) & 0x3ff) - (f - first) * kUnroll;
+                            run_end = nxt_start < f_end ? nxt_start : f_end;
+#pragma unroll
+                            for (int c = 0; c < D; ++c) xq[c] = xo[c];
+                            tau_hi = to;
                         }
                     };
 #pragma unroll
-                    for (int c = 0; c < NV * 4; ++c) xq[c] = 0.0f;
-                    if (f < f_end) load_run();
+                    for (int c = 0; c < D; ++c) xq[c] = 0.0f;
+                    load_run(f < f_end);
                     for (;;) {
                         const bool busy = f < run_end;
                         if (!__any(busy)) break;
                         const int32_t rem = busy ? left : 0;
                         float w[kUnroll][NV * 4];
-                        const uint32_t tau_hi = __float_as_uint(xq[D]);
                         const int32_t i0 = busy ? pos : 0;          // reads past the run stay inside the padded chunk
 #pragma unroll
                         for (int u = 0; u < kUnroll; ++u) {
@@ -478,8 +486,12 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
 #else
                         if (merge) { __syncthreads(); absorb(); }
 #endif
-                        if (f >= run_end && f < f_end) { ++j; load_run(); }
-                        else if (merge) xq[D] = reinterpret_cast<const float*>(qx + owner * NV)[D];
+                        const bool next_run = f >= run_end && f < f_end;
+                        if (__any(next_run)) {
+                            if (next_run) ++j;
+                            load_run(next_run);
+                        }
+                        if (merge) tau_hi = (uint32_t)__shfl((int)(uint32_t)(s.tau >> 32), owner, 64);   // tightened by the merge
                     }
                 }
                 }
@@ -627,7 +639,7 @@ k_query_tile_sorted(QueryArgs a)
 #else
     constexpr bool kProfiled = false;
 #endif
-    if constexpr ((!COUNT || kProfiled) && !tile_small_lds<KC, D>()) {
+    if constexpr ((!COUNT || kProfiled) && tile_has_flat<KC, D>()) {
         const bool uneven = a.algo == 2 || ((entry >> kOrderFlagBit) & 1);
         if (uneven) {
             tile_body<D, DB, KC, COUNT, LOWER, true>(a, tile, lds64);
@@ -640,10 +652,10 @@ k_query_tile_sorted(QueryArgs a)
 template <int KC, int D>
 constexpr size_t tile_sorted_lds_bytes()
 {
-    const size_t flat = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (flat_chunk<D>() + kUnroll + kQueryBlock) + kFlatTables;
-    const size_t direct = (size_t)kPend * kQueryBlock * 8 + (size_t)stage_vecs<D>() * 16 * (direct_chunk<KC, D>() + kUnroll);
+    const size_t flat = kPendBytes + (size_t)stage_vecs<D>() * 16 * (flat_chunk<KC, D>() + kUnroll) + kFlatTables;
+    const size_t direct = kPendBytes + (size_t)stage_vecs<D>() * 16 * (direct_chunk<KC, D>() + kUnroll);
     const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kDumpStride * 4;
-    const size_t scan = (flat > direct && !tile_small_lds<KC, D>()) ? flat : direct;
+    const size_t scan = (tile_has_flat<KC, D>() && flat > direct) ? flat : direct;
     return scan > out ? scan : out;
 }
 
