@@ -8,7 +8,9 @@
 //     (offsets in the first DB-1 binning dimensions) of the same shell together.  Queries of a
 //     tile are consecutive in bin order, so the bins they need for one column offset form one
 //     contiguous range of sorted points; it is staged through LDS in chunks with coalesced
-//     structure-of-arrays loads, and each lane scans only its own sub-range of the chunk;
+//     structure-of-arrays loads, and each lane scans only its own sub-range of the chunk (direct
+//     scan), or, in tiles whose lanes' sub-ranges differ widely, the passes of all sub-ranges are
+//     dealt out evenly over the lanes whichever query they belong to (flattened scan);
 //   * a candidate that beats the lane's current k-th best is appended to a small per-lane
 //     pending buffer in LDS (one write, no ordering work).  When any lane's buffer is full, and
 //     at the end of every shell, all lanes absorb their pending keys into the sorted register
@@ -16,7 +18,10 @@
 //   * keys are 64-bit (distance bits << 32 | original index); slots beyond K-1 are pinned with
 //     zero keys so that the last register is always the last wanted key (list sizes 16/32/48/64; longer
 //     lists take a second pass that counts only keys above the first pass's last one);
-//   * finished rows leave through LDS so that each output row is written as contiguous bytes;
+//   * finished rows leave from the registers in 16-byte pieces when K equals the list size, else
+//     through LDS so that each output row is written as contiguous bytes;
+//   * the stage takes what the LDS budget of a workgroup leaves, and that budget is what lets as
+//     many workgroups share a CU as the registers allow;
 //   * lanes still uncertified when few are left are handed to the list kernel.
 #pragma once
 #include "fg_query.hpp"
@@ -108,7 +113,8 @@ template <int D, int DB, int KC, bool COUNT, bool LOWER, bool FLAT>
 __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile, uint64_t* lds64)
 {
     constexpr int CHUNK = FLAT ? flat_chunk<KC, D>() : direct_chunk<KC, D>();
-    // LDS: [pending kPend x 64 keys][stage (D+1) x kStageChunk words]; re-used at the end as
+    // LDS: [pending kPend x 64 keys][stage: CHUNK + kUnroll points of NV float4s][tables of the flattened scan];
+    //      re-used at the end as
     //      [rows 64 words][KC x 64 words of the sorted lists, indices first, distances second]
     const int lane = threadIdx.x;
     // pending keys: index words [kPend][64], then distance words [kPend][64]
@@ -120,7 +126,7 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
     const uint32_t pend_base = (uint32_t)(uintptr_t)(lds_word*)pend_lds;
     uint32_t pend_top = pend_base;
     constexpr int NV = stage_vecs<D>();
-    float4* stage = reinterpret_cast<float4*>(lds64 + kPend * kQueryBlock);   // [kStageChunk][NV]
+    float4* stage = reinterpret_cast<float4*>(lds64 + kPend * kQueryBlock);   // [CHUNK + kUnroll][NV]
     // flattened scan only: after the stage, [64] pending counts, [64] run descriptors, [66] run starts in the
     // flattened order, [64] lower bounds
     uint32_t* const pend_cnt = reinterpret_cast<uint32_t*>(stage + (CHUNK + kUnroll) * NV);
