@@ -23,10 +23,6 @@
 namespace fg {
 
 constexpr int kQueryBlock = 64;                    // one wavefront per workgroup
-#ifndef FG_STAGE_CHUNK
-#define FG_STAGE_CHUNK 256
-#endif
-constexpr int kStageChunk = FG_STAGE_CHUNK;       // points staged through LDS per chunk (tile kernel)
 constexpr float kBoundShrink = 0.99999618530273f;  // 1 - 2^-18: covers fp32 rounding of d2 and of the bound
 
 // Per-lane geometry of one query: its coordinates, its bin, its row split's grid, and the
@@ -114,9 +110,6 @@ struct ShellSearch : LaneGeom<D, DB> {
     const int32_t* __restrict__ dir;
     int64_t stride;
     int32_t self_pos, cap, filled, cand;
-#ifdef FG_DEBUG_SHELLS
-    int32_t last_r = 0;
-#endif
 
     __device__ __forceinline__ void sift_down(uint64_t key, int32_t size)
     {
@@ -216,12 +209,7 @@ struct ShellSearch : LaneGeom<D, DB> {
         if (cap <= 0) return;
         for (int32_t r = 0;; ++r) {      // ends at the latest when the cube covers the grid (r = n_bins - 1)
             visit<0>(r, 0, 0.0f, r == 0);
-            if (certified(r)) {
-#ifdef FG_DEBUG_SHELLS
-                last_r = r;
-#endif
-                break;
-            }
+            if (certified(r)) break;
         }
     }
 
@@ -268,9 +256,7 @@ __device__ __forceinline__ void write_row(ShellSearch<D, DB, COUNT>& s, const Qu
             od[j + 1] = 0.0f;
         }
     }
-#ifndef FG_TILE_PROF
     if (COUNT) a.out_cand[row] = (add_count ? a.out_cand[row] : 0) + s.cand;
-#endif
 }
 
 // Wave-wide min / max of one int per lane with DPP row shifts and row broadcasts (6 VALU

@@ -16,7 +16,10 @@
 // A far-searching query therefore costs a few memory round trips per shell, not one per bin.
 // The tile kernel has already searched the first shells of every query it hands over: its list so
 // far sits in the query's output row and the first unsearched shell in slot 0 of the distance row,
-// so the search resumes there with a k-th best that already prunes most of the new shell.
+// so the search resumes there with a k-th best that already prunes most of the new shell.  The tile
+// kernel searches the union of what the 16 queries of a row need, so that list may hold points
+// from beyond the shells named as searched: a candidate whose key is already in the list it
+// started with is dropped (keys are unique per point).
 // A pass finds at most 64 neighbours; longer lists take two passes (see the launch code).
 #pragma once
 #include "fg_query.hpp"
@@ -66,6 +69,7 @@ __global__ void __launch_bounds__(kQueryBlock)
 k_query_list_wave(QueryArgs a)
 {
     __shared__ uint64_t pend[kListPend];
+    __shared__ uint64_t given[kQueryBlock];         // the list the query arrived with, ascending
     __shared__ int32_t seg_excl[kQueryBlock], seg_a1[kQueryBlock], seg_len1[kQueryBlock], seg_a2[kQueryBlock];
     const int lane = threadIdx.x;
     const int32_t count = *a.work_count;
@@ -93,6 +97,8 @@ k_query_list_wave(QueryArgs a)
         }
         const int32_t R0 = __float_as_int(od[0]);
         s.tau = __shfl(best, kQueryBlock - 1, 64);
+        given[lane] = best;
+        __syncthreads();
         int32_t npend = 0, cand = 0;
 
         auto absorb64 = [&]() {                     // merges pend[0..min(npend,64)) into the best list
@@ -200,7 +206,14 @@ k_query_list_wave(QueryArgs a)
                     const int32_t src = a.perm[q];
                     const bool live = in && q != p && !(a.dir && !dir_is_neighbour(a.dir[src]));
                     const uint64_t key = ((uint64_t)__float_as_uint(d2) << 32) | (uint32_t)src;
-                    const bool acc = live && key < s.tau && (a.slot0 == 0 || key > lower);
+                    bool acc = live && key < s.tau && (a.slot0 == 0 || key > lower);
+                    if (acc) {                      // already in the list it came with?
+                        int32_t lo = 0;
+#pragma unroll
+                        for (int step = kQueryBlock / 2; step > 0; step >>= 1)
+                            if (given[lo + step - 1] < key) lo += step;
+                        acc = given[lo] != key;
+                    }
                     if (COUNT) cand += __popcll(__ballot(live));
                     const uint64_t m = __ballot(acc);
                     if (m) {
@@ -223,9 +236,7 @@ k_query_list_wave(QueryArgs a)
             oi[j] = real ? (int32_t)(uint32_t)best : -1;
             od[j] = real ? __uint_as_float((uint32_t)(best >> 32)) : 0.0f;
         }
-#ifndef FG_TILE_PROF
         if (COUNT && lane == 0) a.out_cand[row] += cand;
-#endif
         __syncthreads();
     }
 }

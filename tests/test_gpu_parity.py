@@ -219,11 +219,10 @@ def test_tile_and_list_kernels_both_run_and_agree_with_the_plain_walk():
 
 @pytest.mark.parametrize("d,k", [(2, 20), (3, 9), (3, 16), (3, 32), (3, 40), (3, 64), (4, 33), (5, 25), (6, 48), (8, 64), (10, 20),
                                  (3, 100), (3, 128)])
-def test_flattened_scan_on_every_tile(d, k):
-    """query_algo = 2: the tile kernel's flattened scan (the work of a chunk dealt out evenly over the lanes,
-    kept candidates appended to their query's pending buffer from any lane) on every tile, for every list size
-    and both passes of a long list.  Clustered points with duplicates, a short and an empty split, direction
-    flags."""
+def test_clustered_points_every_list_size(d, k):
+    """Every list size and both passes of a long list on clustered points with duplicates, a short and an empty
+    split (tiles that straddle row splits walk once per split), with and without direction flags, through the
+    two calls a training step makes (bin, then query on that binning)."""
     rng = np.random.Generator(np.random.PCG64(500 + 10 * d + k))
     sizes = [2300, 5, 0, 1700]
     n = sum(sizes)
@@ -235,24 +234,22 @@ def test_flattened_scan_on_every_tile(d, k):
     oi, od = oracle.knn(x, rs, k)
     for nb in (0, 7):
         bn = B.fg_bin_points(xt, rt, k, nb, min(d, 3) if nb else 0)
-        bn.raw.query_algo = 2
         gi, gd = B.fg_query_binned(bn, rt, k)
         torch.cuda.synchronize()
-        assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "flattened d=%d k=%d nb=%d" % (d, k, nb))
+        assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "clustered d=%d k=%d nb=%d" % (d, k, nb))
     direction = rng.integers(0, 4, size=n).astype(np.int32)
     oi, od = oracle.knn(x, rs, k, direction=direction)
     bn = B.fg_bin_points(xt, rt, k)
     dt = torch.from_numpy(direction).to(DEV)
     bn.raw.dir = dt.data_ptr()
-    bn.raw.query_algo = 2
     gi, gd = B.fg_query_binned(bn, rt, k)
     torch.cuda.synchronize()
-    assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "flattened with flags d=%d k=%d" % (d, k))
+    assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "clustered with flags d=%d k=%d" % (d, k))
 
 
-def test_uneven_tiles_take_the_flattened_scan_in_an_ordered_launch():
-    """More than 1024 tiles: the ordering kernels rank the tiles and mark the uneven ones; on clustered points
-    some tiles must be marked (and scanned flattened), on a regular lattice none."""
+def test_ordered_launch_takes_every_tile_once():
+    """More than 1024 tiles: the ordering kernels rank the tiles by estimated work (heaviest first); the order
+    must be a permutation of the tiles, and the result the same as the plain walk's."""
     rng = np.random.Generator(np.random.PCG64(77))
     n, k = 90_000, 32
     centres = rng.random((40, 3)) * 10.0
@@ -266,10 +263,9 @@ def test_uneven_tiles_take_the_flattened_scan_in_an_ordered_launch():
     torch.cuda.synchronize()
     n_tiles = (n + 63) // 64
     order = bn._view(bn.raw.tile_order, 2 * n_tiles + 128, torch.int32).cpu().numpy()
-    tiles, flags = order[:n_tiles] & ((1 << 30) - 1), order[:n_tiles] >> 30
+    tiles, classes = order[:n_tiles], order[n_tiles:2 * n_tiles]
     assert np.array_equal(np.sort(tiles), np.arange(n_tiles))               # a permutation of the tiles
-    assert 0 < flags.sum() < n_tiles
-    assert np.array_equal(flags, (order[n_tiles:2 * n_tiles][tiles] >> 6) & 1)
+    assert np.all(np.diff(classes[tiles]) <= 0) and classes.min() < classes.max()   # heaviest class first
     rows = np.sort(rng.choice(n, size=3000, replace=False)).astype(np.int64)
     oi, od = oracle.knn_rows(x, rs, k, rows)
     gi, gd = gi.cpu().numpy(), gd.cpu().numpy()

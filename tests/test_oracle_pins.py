@@ -424,3 +424,61 @@ def test_backward_by_hand_and_padding():
     idx_pad = np.array([[0, -1], [1, -1], [2, -1]], dtype=np.int32)
     grad, asum = oracle.knn_backward(g, idx_pad, x)
     assert np.all(grad == 0.0) and np.all(asum == 0.0)
+
+
+def test_backward_abs_sum_by_hand():
+    """abs_sum is the scale of every gradient tolerance: per element, the sum of |2 g (x_v - x_u)| over the
+    edges that touch it, at both ends.  Same three collinear points as above, worked by hand:
+    edge 0->1 (g=1): |2*1*(0-1)| = 2 on points 0 and 1; edge 1->0 (g=2): |2*2*(1-0)| = 4 on points 1 and 0;
+    edge 2->1 (g=3): |2*3*(3-1)| = 12 on points 2 and 1; the self entries of slot 0 contribute |0|."""
+    x = np.array([[0, 0], [1, 0], [3, 0]], dtype=np.float32)
+    idx = np.array([[0, 1], [1, 0], [2, 1]], dtype=np.int32)
+    g = np.array([[5, 1], [7, 2], [9, 3]], dtype=np.float32)
+    grad, asum = oracle.knn_backward(g, idx, x)
+    assert asum[:, 0].tolist() == [6.0, 18.0, 12.0] and np.all(asum[:, 1] == 0.0)
+    # signs flipped on the upstream gradient: the gradient flips, the scale does not
+    grad2, asum2 = oracle.knn_backward(-g, idx, x)
+    assert np.array_equal(grad2, -grad) and np.array_equal(asum2, asum)
+    # an off-axis pair: edge 0->1 only, g = 0.5, x0 = (1, 2), x1 = (4, -2): |2*0.5*(-3)| = 3, |2*0.5*4| = 4 at both ends
+    x = np.array([[1, 2], [4, -2]], dtype=np.float32)
+    idx = np.array([[0, 1], [1, -1]], dtype=np.int32)
+    g = np.array([[0.0, 0.5], [0.0, 0.0]], dtype=np.float32)
+    grad, asum = oracle.knn_backward(g, idx, x)
+    assert asum.tolist() == [[3.0, 4.0], [3.0, 4.0]] and grad.tolist() == [[-3.0, 4.0], [3.0, -4.0]]
+
+
+def test_backward_abs_sum_recomputed():
+    """abs_sum against a float64 numpy scatter of the absolute contributions over the same index matrix, and
+    the properties that fix its scale: it bounds |grad| element by element, equals |grad| where no
+    contribution cancels (all contributions of one sign), and doubles when the upstream gradient doubles."""
+    sizes = [400, 37, 600]
+    n = sum(sizes)
+    x, rs = W.uniform(n, 3, seed=81, sizes=sizes)
+    k = 12
+    idx, _ = oracle.knn(x, rs, k)
+    idx[5, 7:] = -1                                            # some padding
+    g = W.upstream_grad(n, k, seed=82)
+    grad, asum = oracle.knn_backward(g, idx, x)
+    x64, g64 = x.astype(np.float64), g.astype(np.float64)
+    want_a = np.zeros((n, 3))
+    want_g = np.zeros((n, 3))
+    v = np.repeat(np.arange(n), k)
+    u = idx.reshape(-1)
+    keep = u >= 0
+    v, u, gg = v[keep], u[keep], g64.reshape(-1)[keep]
+    t = 2.0 * gg[:, None] * (x64[v] - x64[u])
+    np.add.at(want_g, v, t)
+    np.add.at(want_g, u, -t)
+    np.add.at(want_a, v, np.abs(t))
+    np.add.at(want_a, u, np.abs(t))
+    assert np.allclose(asum, want_a, rtol=1e-12, atol=0) and np.allclose(grad, want_g, rtol=0, atol=1e-12 * want_a.max())
+    assert np.all(asum >= np.abs(grad) * (1 - 1e-12))
+    # one outgoing edge per row towards a point at larger coordinates, positive upstream gradient: at the source
+    # every contribution is negative, so |grad| == abs_sum there exactly when nothing comes in
+    xs = np.cumsum(np.ones((50, 3), dtype=np.float32), axis=0)
+    idx1 = np.stack([np.arange(50), np.minimum(np.arange(50) + 1, 49)], axis=1).astype(np.int32)
+    g1 = np.abs(W.upstream_grad(50, 2, seed=83)) + 0.1
+    gr1, as1 = oracle.knn_backward(g1, idx1, xs)
+    assert np.array_equal(np.abs(gr1[0]), as1[0]) and np.all(as1[0] > 0)
+    _, asum2 = oracle.knn_backward(2.0 * g, idx, x)
+    assert np.allclose(asum2, 2.0 * asum, rtol=1e-12, atol=0)
