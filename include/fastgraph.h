@@ -53,7 +53,7 @@ const char* fg_status_string(fg_status status);
 
 /* Bins per dimension and number of binning dimensions (Section 3, the equation
  *   n_bins = (32 * n_elems / K)^(1/d_max), n_elems = mean points per row split,
- * "clamped to [5, 30]", and the paragraph limiting binning to the first <= 5 dimensions).
+ * its clamp to the range 5..30, and the paragraph limiting binning to the first <= 5 dimensions).
  *   mode 0: the paper's heuristic as printed: d_bin = min(d, 5), value truncated, clamped to [5,30].
  *   mode 1: tuned for MI355X: same functional form with this build's own constant, binning
  *           dimensions and upper clamp (a finer grid; the paper notes the value is hardware
@@ -65,14 +65,17 @@ fg_status fg_auto_n_bins(int64_t n, int32_t n_segments, int32_t k, int32_t d, in
 
 /* Bytes of workspace needed by fg_bin_points / fg_binned_select_knn / fg_knn_backward for this
  * problem (n_bins <= 0 or d_bin <= 0: the values fg_auto_n_bins mode 1 would choose).
- * bytes: host out.  O(n * (d + 5) + n_segments * n_bins^d_bin) words ("virtually no memory
- * overhead", Abstract). */
+ * bytes: host out.  O(n * (d + 5) + n_segments * n_bins^d_bin) words: a few words per point beyond
+ * the input (the Abstract's claim of a negligible memory overhead). */
 fg_status fg_workspace_size(int64_t n, int32_t d, int32_t n_segments, int32_t k,
                             int32_t n_bins, int32_t d_bin, size_t* bytes);
 
 /* Result of the binning stage: device pointers into the caller's workspace. */
 typedef struct {
-    const int32_t* bin_idx;    /* [n]  flat bin of each point, ORIGINAL order; segment s owns bins [s*T, (s+1)*T) */
+    const int32_t* bin_idx;    /* [n]  bin number of each point, ORIGINAL order; segment s owns bins [s*T, (s+1)*T).
+                                  Inside a segment bins are numbered in serpentine order over the grid: the digit of
+                                  binning dimension c (most significant first) runs backwards when the number formed by
+                                  the digits before it is odd, so that consecutive bin numbers are neighbours in space */
     const int32_t* perm;       /* [n]  sorted position -> original row index */
     const int32_t* bin_bounds; /* [n_segments*T + 1] exclusive prefix of bin populations: bin b holds
                                   sorted positions [bin_bounds[b], bin_bounds[b+1]) */
@@ -83,29 +86,30 @@ typedef struct {
     int64_t cells_per_segment; /* T = n_bins^d_bin */
     int32_t n_bins;            /* bins per binning dimension actually used */
     int32_t d_bin;             /* binning dimensions actually used (the first d_bin coordinates) */
-    int32_t* work_list;        /* [n]  scratch of the query stage: queries handed from the tile kernel to the list kernel */
-    int32_t* work_count;       /* [1]  scratch of the query stage */
-    const int32_t* dir;        /* [n] direction flags in ORIGINAL row order for the query stage, or NULL (set to NULL
-                                  by fg_bin_points; see fg_binned_select_knn_dir) */
-    int32_t query_algo;        /* 0 (set by fg_bin_points): tile kernel + list kernel; 1: the one-lane-per-query
-                                  shell walk for every query (slower; same result; kept for cross-checking);
-                                  2: as 0, with the tile kernel's flattened scan for every tile instead of the
-                                  uneven ones only (same result; for tests) */
-    int32_t defer_lanes;       /* tuning knob of the tile kernel, 0..64 (set by fg_bin_points): after shell 1 a
-                                  wavefront goes on to the next shell only while more than this many of its 64
-                                  queries are unfinished (and its lanes have been evenly loaded so far); the
-                                  rest go to the list kernel.  Result-neutral. */
-    int32_t* tile_order;       /* [2*ceil(n/64) + 128]  scratch of the query stage: the order in which the tile
-                                  kernel takes its tiles of 64 bin-ordered queries (most work first) */
+    void* scratch;             /* opaque: scratch of the query stage inside the workspace.  Its first int32 holds, after
+                                  fg_query_binned, the number of queries the tile kernel handed to the list kernel (a
+                                  diagnostic; nothing else in it is meant to be read) */
 } fg_binning;
 
-/* Spatial partition + counting sort (Section 3: "points are sorted by bin assignments and
- * cumulative boundaries are created for each bin"; Algorithm 2 inputs binIdx, binBounds,
- * binCounts, binWidths; Algorithm 1's row-major flattening with the last dimension fastest).
+/* Options of the query stage; none changes the result.  A NULL pointer means all defaults. */
+typedef struct {
+    const int32_t* dir;        /* [n] direction flags in ORIGINAL row order (see fg_binned_select_knn_dir), or NULL */
+    int32_t algo;              /* 0: tile kernel + list kernel (default); 1: the one-lane-per-query shell walk for
+                                  every query (slower; kept for cross-checking) */
+    int32_t defer_lanes;       /* after shell 1 a wavefront of the tile kernel goes on to the next shell only while
+                                  more than this many of its 64 queries are unfinished, the rest go to the list
+                                  kernel; 0..64, negative: the default */
+} fg_query_options;
+
+/* Spatial partition + counting sort (Section 3, second paragraph: bins per row split, points ordered by bin,
+ * cumulative bin boundaries; Algorithm 2 inputs binIdx, binBounds, binCounts, binWidths).  The paper numbers
+ * bins row-major (Algorithm 1); here the numbering is serpentine (see bin_idx), which keeps runs of the last
+ * dimension contiguous and makes consecutive points in bin order neighbours in space.
  * Per row split: bounding box over the first d_bin coordinates; bin of a point in dimension c =
  * min(n_bins-1, floor((x_c - lo_c) * n_bins / (hi_c - lo_c))), 0 if hi_c == lo_c.
  *   coords      [n][d] row-major float32
  *   row_splits  [n_segments+1] int32
+ *   k_hint      the K of the search that will follow (only the automatic bin count depends on it)
  *   n_bins      bins per dimension, <= 0: auto (mode 1);  d_bin likewise
  *   view        host out: where the results live inside `workspace`
  * The order of points inside one bin is unspecified.  n == 0: FG_OK, nothing enqueued. */
@@ -151,10 +155,12 @@ fg_status fg_binned_select_knn_counted(const float* coords, const int32_t* row_s
 
 /* Query stage alone on an existing binning (what fg_binned_select_knn runs after
  * fg_bin_points); `view` must come from fg_bin_points on the same coords/row_splits and its
- * workspace must still be intact.  Used to time the query kernel on its own. */
+ * workspace must still be intact.  Used to time the query kernel on its own.
+ * options: host pointer, may be NULL. */
 fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int64_t n, int32_t d,
                           int32_t n_segments, int32_t k, int32_t* out_idx, float* out_d2,
-                          int32_t* out_candidates /* may be NULL */, void* stream);
+                          int32_t* out_candidates /* may be NULL */, const fg_query_options* options,
+                          void* stream);
 
 /* Backward of the squared distances (Section 3, last paragraph):
  *   grad_coords[v][c]  = sum_j grad_d2[v][j] * 2 * (x[v][c] - x[idx[v][j]][c])

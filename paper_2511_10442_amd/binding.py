@@ -38,9 +38,11 @@ class _Binning(ctypes.Structure):
                 ("bin_bounds", ctypes.c_void_p), ("sorted_soa", ctypes.c_void_p),
                 ("seg_geom", ctypes.c_void_p), ("soa_stride", ctypes.c_int64),
                 ("cells_per_segment", ctypes.c_int64), ("n_bins", ctypes.c_int32),
-                ("d_bin", ctypes.c_int32), ("work_list", ctypes.c_void_p),
-                ("work_count", ctypes.c_void_p), ("dir", ctypes.c_void_p), ("query_algo", ctypes.c_int32),
-                ("defer_lanes", ctypes.c_int32), ("tile_order", ctypes.c_void_p)]
+                ("d_bin", ctypes.c_int32), ("scratch", ctypes.c_void_p)]
+
+
+class _QueryOptions(ctypes.Structure):
+    _fields_ = [("dir", ctypes.c_void_p), ("algo", ctypes.c_int32), ("defer_lanes", ctypes.c_int32)]
 
 
 _lib = None
@@ -72,7 +74,8 @@ def lib() -> ctypes.CDLL:
         L.fg_binned_select_knn_counted.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp,
                                                    vp, sz, vp]
         L.fg_query_binned.restype = ctypes.c_int
-        L.fg_query_binned.argtypes = [ctypes.POINTER(_Binning), vp, i64, i32, i32, i32, vp, vp, vp, vp]
+        L.fg_query_binned.argtypes = [ctypes.POINTER(_Binning), vp, i64, i32, i32, i32, vp, vp, vp,
+                                      ctypes.POINTER(_QueryOptions), vp]
         L.fg_knn_backward.restype = ctypes.c_int
         L.fg_knn_backward.argtypes = [vp, vp, vp, vp, i64, i32, i32, i32, vp, vp, sz, vp]
         L.fg_knn_backward_binned.restype = ctypes.c_int
@@ -169,8 +172,9 @@ class Binning:
 
     @property
     def work_count(self):
-        """Number of queries the tile kernel handed to the list kernel in the last query call."""
-        return self._view(self.raw.work_count, 1, torch.int32)
+        """Number of queries the tile kernel handed to the list kernel in the last query call (the one word of
+        the scratch block that the header documents)."""
+        return self._view(self.raw.scratch, 1, torch.int32)
 
     @property
     def seg_geom(self):
@@ -194,18 +198,38 @@ def fg_bin_points(coords: torch.Tensor, row_splits: torch.Tensor, k_hint: int, n
                    int(raw.cells_per_segment), int(raw.soa_stride))
 
 
+def _out(t, shape, dtype, device, name: str) -> torch.Tensor:
+    """A caller-supplied output tensor must be exactly what the kernels write: device, dtype, shape, contiguous."""
+    if t is None:
+        return torch.empty(shape, dtype=dtype, device=device)
+    _dev(t, dtype, name)
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    return t
+
+
 def fg_query_binned(binning: Binning, row_splits: torch.Tensor, k: int, out_idx=None, out_d2=None,
-                    out_candidates=None):
+                    out_candidates=None, direction: torch.Tensor | None = None, algo: int = 0,
+                    defer_lanes: int = -1):
+    """direction, algo, defer_lanes: the fields of fg_query_options (None / 0 / -1 = defaults)."""
     row_splits = _dev(row_splits, torch.int32, "row_splits")
     n = binning.n
     dev = binning.workspace.device
-    if out_idx is None:
-        out_idx = torch.empty((n, k), dtype=torch.int32, device=dev)
-    if out_d2 is None:
-        out_d2 = torch.empty((n, k), dtype=torch.float32, device=dev)
+    out_idx = _out(out_idx, (n, k), torch.int32, dev, "out_idx")
+    out_d2 = _out(out_d2, (n, k), torch.float32, dev, "out_d2")
+    if out_candidates is not None:
+        _out(out_candidates, (n,), torch.int32, dev, "out_candidates")
+    opt = _QueryOptions()
+    if direction is not None:
+        direction = _dev(direction, torch.int32, "direction")
+        if direction.numel() != n:
+            raise ValueError("direction must have one flag per point")
+    opt.dir = _ptr(direction) or None
+    opt.algo = algo
+    opt.defer_lanes = defer_lanes
     _check(lib().fg_query_binned(ctypes.byref(binning.raw), _ptr(row_splits), n, binning.d,
                                  binning.n_segments, k, _ptr(out_idx), _ptr(out_d2),
-                                 _ptr(out_candidates), _stream()), "fg_query_binned")
+                                 _ptr(out_candidates), ctypes.byref(opt), _stream()), "fg_query_binned")
     return out_idx, out_d2
 
 
@@ -218,10 +242,8 @@ def fg_binned_select_knn(coords: torch.Tensor, row_splits: torch.Tensor, k: int,
     s = row_splits.numel() - 1
     if workspace is None:
         workspace = alloc_workspace(n, d, s, k, n_bins, d_bin, coords.device)
-    if out_idx is None:
-        out_idx = torch.empty((n, k), dtype=torch.int32, device=coords.device)
-    if out_d2 is None:
-        out_d2 = torch.empty((n, k), dtype=torch.float32, device=coords.device)
+    out_idx = _out(out_idx, (n, k), torch.int32, coords.device, "out_idx")
+    out_d2 = _out(out_d2, (n, k), torch.float32, coords.device, "out_d2")
     _check(lib().fg_binned_select_knn(_ptr(coords), _ptr(row_splits), n, d, s, k, n_bins, d_bin,
                                       _ptr(out_idx), _ptr(out_d2), _ptr(workspace),
                                       workspace.numel(), _stream()), "fg_binned_select_knn")
@@ -241,10 +263,8 @@ def fg_binned_select_knn_dir(coords: torch.Tensor, row_splits: torch.Tensor, dir
     s = row_splits.numel() - 1
     if workspace is None:
         workspace = alloc_workspace(n, d, s, k, n_bins, d_bin, coords.device)
-    if out_idx is None:
-        out_idx = torch.empty((n, k), dtype=torch.int32, device=coords.device)
-    if out_d2 is None:
-        out_d2 = torch.empty((n, k), dtype=torch.float32, device=coords.device)
+    out_idx = _out(out_idx, (n, k), torch.int32, coords.device, "out_idx")
+    out_d2 = _out(out_d2, (n, k), torch.float32, coords.device, "out_d2")
     _check(lib().fg_binned_select_knn_dir(_ptr(coords), _ptr(row_splits), _ptr(direction), n, d, s, k, n_bins,
                                           d_bin, _ptr(out_idx), _ptr(out_d2), _ptr(workspace),
                                           workspace.numel(), _stream()), "fg_binned_select_knn_dir")
@@ -282,8 +302,7 @@ def fg_knn_backward(grad_d2: torch.Tensor, idx: torch.Tensor, coords: torch.Tens
     k = idx.shape[1]
     if tuple(grad_d2.shape) != (n, k) or idx.shape[0] != n:
         raise ValueError("grad_d2 and idx must be [n, k]")
-    if grad_coords is None:
-        grad_coords = torch.empty((n, d), dtype=torch.float32, device=coords.device)
+    grad_coords = _out(grad_coords, (n, d), torch.float32, coords.device, "grad_coords")
     s = 0
     if row_splits is not None:
         row_splits = _dev(row_splits, torch.int32, "row_splits")
@@ -308,8 +327,7 @@ def fg_knn_backward_binned(binning: Binning, grad_d2: torch.Tensor, idx: torch.T
     k = idx.shape[1]
     if tuple(grad_d2.shape) != (n, k) or idx.shape[0] != n or n != binning.n or d != binning.d:
         raise ValueError("grad_d2 and idx must be [n, k] for the binned coords [n, d]")
-    if grad_coords is None:
-        grad_coords = torch.empty((n, d), dtype=torch.float32, device=coords.device)
+    grad_coords = _out(grad_coords, (n, d), torch.float32, coords.device, "grad_coords")
     _check(lib().fg_knn_backward_binned(ctypes.byref(binning.raw), _ptr(grad_d2), _ptr(idx), _ptr(coords), n, d, k,
                                         _ptr(grad_coords), _stream()), "fg_knn_backward_binned")
     return grad_coords

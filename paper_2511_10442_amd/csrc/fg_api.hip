@@ -56,8 +56,25 @@ constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
+// The query stage's scratch block (fg_binning::scratch): hand-over counter first (the one word documented in the
+// header), then the work list, the tile order and an [n] array that the counting sort uses for the ranks inside
+// the bins and the query stage afterwards for the candidate permutation masked by direction flags.
+struct ScratchLayout { size_t work_count, work_list, tile_order, rank, total; };
+
+ScratchLayout scratch_layout(int64_t n)
+{
+    ScratchLayout S;
+    size_t off = 0;
+    S.work_count = off; off = align_up(off + sizeof(int32_t));
+    S.work_list = off;  off = align_up(off + sizeof(int32_t) * (size_t)n);
+    S.tile_order = off; off = align_up(off + sizeof(int32_t) * (size_t)(2 * ((n + 63) / 64) + 128));
+    S.rank = off;       off = align_up(off + sizeof(int32_t) * (size_t)n);
+    S.total = off;
+    return S;
+}
+
 struct Layout {
-    size_t keys, geom, bin_idx, rank, perm, soa, bounds, partials, work_list, work_count, tile_order, total;
+    size_t keys, geom, bin_idx, perm, soa, bounds, partials, scratch, total;
     int64_t soa_stride, total_bins, cells_per_segment;
 };
 
@@ -74,15 +91,12 @@ Layout make_layout(int64_t n, int32_t d, int32_t n_segments, int32_t n_bins, int
     L.keys = off;     off = align_up(off + sizeof(uint32_t) * 2 * (size_t)n_segments * d_bin * kKeyStride);
     L.geom = off;     off = align_up(off + sizeof(float) * kGeomStride * (size_t)n_segments * d_bin);
     L.bin_idx = off;  off = align_up(off + sizeof(int32_t) * (size_t)n);
-    L.rank = off;     off = align_up(off + sizeof(int32_t) * (size_t)n);
     L.perm = off;     off = align_up(off + sizeof(int32_t) * (size_t)n);
     // d = 3: room for four floats per point, because the backward keeps a padded copy of the rows here
     L.soa = off;      off = align_up(off + sizeof(float) * (size_t)L.soa_stride * (d == 3 ? 4 : d));
     L.bounds = off;   off = align_up(off + sizeof(int32_t) * (size_t)(L.total_bins + 1));
     L.partials = off; off = align_up(off + sizeof(int32_t) * (size_t)((L.total_bins + 1 + kScanChunkHost - 1) / kScanChunkHost));
-    L.work_list = off; off = align_up(off + sizeof(int32_t) * (size_t)n);
-    L.work_count = off; off = align_up(off + sizeof(int32_t));
-    L.tile_order = off; off = align_up(off + sizeof(int32_t) * (size_t)(2 * ((n + 63) / 64) + 128));
+    L.scratch = off;  off = align_up(off + scratch_layout(n).total);
     L.total = off;
     return L;
 }
@@ -224,16 +238,11 @@ static fg_status bin_points_impl(const float* coords, const int32_t* row_splits,
     view->cells_per_segment = L.cells_per_segment;
     view->n_bins = n_bins;
     view->d_bin = d_bin;
-    view->work_list = (int32_t*)(ws + L.work_list);
-    view->work_count = (int32_t*)(ws + L.work_count);
-    view->tile_order = (int32_t*)(ws + L.tile_order);
-    view->dir = nullptr;
-    view->query_algo = 0;
-    view->defer_lanes = kDefaultDeferLanes;
+    view->scratch = ws + L.scratch;
     if (n == 0) return FG_OK;
     hipError_t e = launch_binning(coords, row_splits, (int32_t)n, d, n_segments, n_bins, d_bin, L.total_bins,
                                   (uint32_t*)(ws + L.keys), (float*)(ws + L.geom), (int32_t*)(ws + L.bin_idx),
-                                  (int32_t*)(ws + L.rank), (int32_t*)(ws + L.perm), (float*)(ws + L.soa),
+                                  (int32_t*)(ws + L.scratch + scratch_layout(n).rank), (int32_t*)(ws + L.perm), (float*)(ws + L.soa),
                                   L.soa_stride, (int32_t*)(ws + L.bounds), (int32_t*)(ws + L.partials), morton_bits,
                                   (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
@@ -254,14 +263,14 @@ fg_status fg_bin_points(const float* coords, const int32_t* row_splits, int64_t 
 
 fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int64_t n, int32_t d,
                           int32_t n_segments, int32_t k, int32_t* out_idx, float* out_d2,
-                          int32_t* out_candidates, void* stream)
+                          int32_t* out_candidates, const fg_query_options* options, void* stream)
 {
     if (!view) return FG_ERR_NULL;
     fg_status st = check_problem(n, d, n_segments, k);
     if (st != FG_OK) return st;
     if (n == 0) return FG_OK;
     if (!row_splits || !out_idx || !out_d2 || !view->perm || !view->bin_bounds || !view->sorted_soa ||
-        !view->seg_geom || !view->work_list || !view->work_count)
+        !view->seg_geom || !view->scratch)
         return FG_ERR_NULL;
     if (view->d_bin < FG_MIN_D_BIN || view->d_bin > FG_MAX_D_BIN || view->d_bin > d) return FG_ERR_UNSUPPORTED;
     if (view->n_bins < 1 || view->cells_per_segment < 1 ||
@@ -269,11 +278,24 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
         return FG_ERR_BAD_SHAPE;
     QueryArgs a;
     a.soa = view->sorted_soa; a.perm = view->perm; a.bounds = view->bin_bounds; a.geom = view->seg_geom;
-    a.row_splits = row_splits; a.dir = view->dir; a.out_idx = out_idx; a.out_d2 = out_d2; a.out_cand = out_candidates;
+    const ScratchLayout S = scratch_layout(n);
+    char* sc = (char*)view->scratch;
+    const int32_t* dir = options ? options->dir : nullptr;
+    const int32_t defer = (options && options->defer_lanes >= 0) ? options->defer_lanes : kDefaultDeferLanes;
+    a.row_splits = row_splits; a.dir = dir; a.out_idx = out_idx; a.out_d2 = out_d2; a.out_cand = out_candidates;
     a.soa_stride = view->soa_stride; a.n = (int32_t)n; a.n_segments = n_segments; a.k = k;
     a.n_bins = view->n_bins; a.cells_per_segment = (int32_t)view->cells_per_segment;
-    a.work_list = view->work_list; a.work_count = view->work_count; a.bin_idx = view->bin_idx; a.tile_order = view->tile_order; a.algo = (view->query_algo == 1 || view->query_algo == 2) ? view->query_algo : 0;
-    a.defer_lanes = view->defer_lanes < 0 ? 0 : (view->defer_lanes > 64 ? 64 : view->defer_lanes);
+    a.work_list = (int32_t*)(sc + S.work_list); a.work_count = (int32_t*)(sc + S.work_count);
+    a.bin_idx = view->bin_idx; a.tile_order = (int32_t*)(sc + S.tile_order);
+    a.algo = (options && options->algo == 1) ? 1 : 0;
+    a.defer_lanes = defer > 64 ? 64 : defer;
+    a.perm_cand = view->perm;
+    if (dir) {
+        // candidates that a flag excludes: their entry of the permutation the tile kernel reads becomes -1
+        int32_t* masked = (int32_t*)(sc + S.rank);
+        if (launch_mask_perm(view->perm, dir, (int32_t)n, masked, (hipStream_t)stream) != hipSuccess) return FG_ERR_LAUNCH;
+        a.perm_cand = masked;
+    }
     hipError_t e = launch_query(a, d, view->d_bin, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }
@@ -290,8 +312,11 @@ static fg_status knn_impl(const float* coords, const int32_t* row_splits, const 
     st = fg_bin_points(coords, row_splits, n, d, n_segments, k, n_bins, d_bin, workspace, workspace_bytes, &view,
                        stream);
     if (st != FG_OK) return st;
-    view.dir = dir;
-    return fg_query_binned(&view, row_splits, n, d, n_segments, k, out_idx, out_d2, out_candidates, stream);
+    fg_query_options opt;
+    opt.dir = dir;
+    opt.algo = 0;
+    opt.defer_lanes = -1;
+    return fg_query_binned(&view, row_splits, n, d, n_segments, k, out_idx, out_d2, out_candidates, &opt, stream);
 }
 
 fg_status fg_binned_select_knn(const float* coords, const int32_t* row_splits, int64_t n,

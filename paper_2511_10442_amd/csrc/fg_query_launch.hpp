@@ -73,10 +73,9 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
         int32_t cc[DB], seg_cell0 = 0;
         {
             const int32_t b = live ? a.bin_idx[a.perm[p]] : 0;
-            int32_t r = b % a.cells_per_segment;
+            const int32_t r = b % a.cells_per_segment;
             seg_cell0 = b - r;
-#pragma unroll
-            for (int c = DB - 1; c >= 0; --c) { cc[c] = r % a.n_bins; r /= a.n_bins; }
+            snake_cells<DB>(r, a.n_bins, cc);
         }
         int32_t work = 0, around = 0;
         for (int32_t col = 0; col < ncols; ++col) {
@@ -87,14 +86,15 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
                 const int32_t j = cc[c] + rem % 3 - 1;
                 rem /= 3;
                 ok = ok && j >= 0 && j < a.n_bins;
-                flat = flat * a.n_bins + j;
+                flat = snake_push(flat, ok ? j : 0, a.n_bins);
             }
             int32_t len = 0;
             if (ok) {
                 const int32_t cz = cc[DB - 1];
                 const int32_t za = cz > 0 ? cz - 1 : 0, zb = cz < a.n_bins - 1 ? cz + 1 : a.n_bins - 1;
-                const int32_t row = seg_cell0 + flat * a.n_bins;
-                len = a.bounds[row + zb + 1] - a.bounds[row + za];
+                int32_t f0, f1;
+                snake_run(flat, za, zb, a.n_bins, &f0, &f1);
+                len = a.bounds[seg_cell0 + f1 + 1] - a.bounds[seg_cell0 + f0];
             }
             around += len;
             work += oct_max_i32(len) >> 2;         // in units of four candidates; keeps the sum small
@@ -117,14 +117,15 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
                     const int32_t j = cc[c] + rem % 5 - 2;
                     rem /= 5;
                     ok = ok && j >= 0 && j < a.n_bins;
-                    flat = flat * a.n_bins + j;
+                    flat = snake_push(flat, ok ? j : 0, a.n_bins);
                 }
                 int32_t len = 0;
                 if (ok) {
                     const int32_t cz = cc[DB - 1];
                     const int32_t za = cz > 1 ? cz - 2 : 0, zb = cz < a.n_bins - 2 ? cz + 2 : a.n_bins - 1;
-                    const int32_t row = seg_cell0 + flat * a.n_bins;
-                    len = a.bounds[row + zb + 1] - a.bounds[row + za];
+                    int32_t f0, f1;
+                    snake_run(flat, za, zb, a.n_bins, &f0, &f1);
+                    len = a.bounds[seg_cell0 + f1 + 1] - a.bounds[seg_cell0 + f0];
                 }
                 work += oct_max_i32(len) >> 2;
             }

@@ -144,14 +144,14 @@ k_query_list_wave(QueryArgs a)
                         ok = ok && j >= 0 && j < s.neff[c];
                         const float g = s.gap(c, j, o[c]);
                         partial += g * g;
-                        flat = flat * a.n_bins + j;
+                        flat = snake_push(flat, ok ? j : 0, a.n_bins);
                     }
                 }
                 ok = ok && !s.cannot_improve(partial);
                 int32_t a1 = 0, b1 = 0, a2 = 0, b2 = 0;
                 if (ok) {
                     const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
-                    const int32_t row = s.seg_cell0 + flat * a.n_bins;
+                    int32_t f0, f1;
                     if (surf) {
                         int32_t za = cz - R < 0 ? 0 : cz - R;
                         int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
@@ -165,16 +165,19 @@ k_query_list_wave(QueryArgs a)
                             if (!s.cannot_improve(partial + g * g)) break;
                             --zb;
                         }
-                        a1 = a.bounds[row + za];
-                        b1 = a.bounds[row + zb + 1];
+                        snake_run(flat, za, zb, a.n_bins, &f0, &f1);
+                        a1 = a.bounds[s.seg_cell0 + f0];
+                        b1 = a.bounds[s.seg_cell0 + f1 + 1];
                     } else {
                         if (cz - R >= 0) {
                             const float g = s.gap(DB - 1, cz - R, -R);
-                            if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[row + cz - R]; b1 = a.bounds[row + cz - R + 1]; }
+                            snake_run(flat, cz - R, cz - R, a.n_bins, &f0, &f1);
+                            if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[s.seg_cell0 + f0]; b1 = a.bounds[s.seg_cell0 + f1 + 1]; }
                         }
                         if (cz + R <= nz - 1) {
                             const float g = s.gap(DB - 1, cz + R, R);
-                            if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[row + cz + R]; b2 = a.bounds[row + cz + R + 1]; }
+                            snake_run(flat, cz + R, cz + R, a.n_bins, &f0, &f1);
+                            if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[s.seg_cell0 + f0]; b2 = a.bounds[s.seg_cell0 + f1 + 1]; }
                         }
                     }
                 }

@@ -45,9 +45,12 @@ template <int KC, int D> constexpr int tile_waves()
     return KC <= 16 ? 4 : (KC == 32 ? 3 : (KC == 48 ? (D <= 3 ? 3 : 2) : 2));
 }
 constexpr int kPend = 16;             // pending keys per lane between two merges
+constexpr int kPendRows = kPend + 1;  // and one spare slot that takes the stores of candidates a lane does not keep
 constexpr int kRow = 16;              // queries per sub-tile: one DPP row
 constexpr int kRows = kQueryBlock / kRow;
 constexpr int kStepGroup = 4;         // candidates evaluated between two checks of the pending buffers
+constexpr int kSub = 2;               // candidates per lane in a chunk
+constexpr int kChunk = kSub * kRow;   // candidates of a row in a chunk
 constexpr int kMaxShellCols = 2048;   // columns a row may enumerate in one shell; beyond, its queries go to the list kernel
 
 // row pitch of the output transposition in LDS: 65 words, so that the lanes writing one output row (consecutive
@@ -57,11 +60,11 @@ constexpr int kDumpStride = kQueryBlock + 1;
 // ---- DPP helpers: all within one row of 16 lanes; every lane of the wave must be enabled -----------------
 template <int J> __device__ __forceinline__ int32_t row_bcast_i32(int32_t v)
 {
-    return __builtin_amdgcn_update_dpp(0, v, 0x150 + J, 0xf, 0xf, false);    // row_newbcast:J
+    return __builtin_amdgcn_update_dpp(0, v, 0x150 + J, 0xf, 0xf, true);     // row_newbcast:J
 }
 template <int J> __device__ __forceinline__ float row_bcast_f32(float v)
 {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x150 + J, 0xf, 0xf, false));
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x150 + J, 0xf, 0xf, true));
 }
 // reductions over the 16 lanes of a row, result in all of them: butterflies inside quads, across quads of a
 // half row (half mirror), across the halves (mirror)
@@ -130,7 +133,7 @@ __device__ __forceinline__ void store_row_from_registers(const uint64_t (&best)[
 
 // LDS of a workgroup (one wavefront): the pending buffers (8 KB) and the run tables of the four rows (1 KB);
 // at the end the same memory carries the output transposition.
-constexpr size_t kPendBytes = (size_t)kPend * kQueryBlock * 8;
+constexpr size_t kPendBytes = (size_t)kPendRows * kQueryBlock * 8;
 constexpr size_t kRunTableBytes = (size_t)kQueryBlock * 4 * 4;
 template <int KC> constexpr size_t tile_lds_bytes()
 {
@@ -144,7 +147,7 @@ template <int KC> constexpr size_t tile_lds_bytes()
 // (NaN in a lane that must keep nothing); INTRA: the candidates are the row's own queries, lane J skips itself.
 template <int J, int D, bool LOWER, bool INTRA>
 __device__ __forceinline__ void scan_step(const float (&c)[D], int32_t ci, const float (&xq)[D], uint32_t tau_hi,
-                                          uint64_t lower, uint32_t& pend_top, int rl)
+                                          uint64_t lower, uint32_t& pend_top, uint32_t spare, int rl)
 {
     // (candidate - query) squared equals (query - candidate) squared bit for bit; summed left to right
     float diff = row_bcast_f32<J>(c[0]) - xq[0];
@@ -158,15 +161,27 @@ __device__ __forceinline__ void scan_step(const float (&c)[D], int32_t ci, const
     const uint32_t bits = __float_as_uint(d2);
     // kept if its distance does not exceed the k-th best's (a tie on the distance may lose on the index: the
     // merge decides); NaN patterns (poisoned candidates, switched-off queries) lie above every bound
-    bool keep = bits <= tau_hi;
-    if (INTRA) keep = keep && rl != J;
-    if (LOWER) keep = keep && ((((uint64_t)bits << 32) | idx) > lower);
-    if (keep) {
-        // index word and distance word kPend planes apart, then the slot pointer moves on: written out because
-        // the compiler spends a third instruction on a register copy
-        static_assert(kPend * kQueryBlock * 4 == 16 * 256 && kQueryBlock * 4 == 0x100, "offsets below");
-        asm volatile("ds_write2st64_b32 %0, %1, %2 offset1:16\n\tv_add_u32 %0, 0x100, %0"
-                     : "+v"(pend_top) : "v"(idx), "v"(bits) : "memory");
+    // No branch and no change of the execution mask: every lane stores every candidate at its slot pointer, and
+    // only a lane that keeps the candidate moves the pointer on, so what is not kept is overwritten by the next
+    // store.  (Narrowing the mask per step made every step a chain of vector compare -> scalar mask -> store ->
+    // scalar restore that three wavefronts per SIMD cannot hide.)  Index word and distance word are kPendRows
+    // planes apart.
+    static_assert(kPendRows == 17 && kQueryBlock * 4 == 0x100, "offsets below");
+    if constexpr (!INTRA && !LOWER) {
+        // A candidate that is not kept has a distance above the k-th best's, so it does no harm where it stays
+        // if nothing overwrites it: the merge reads all kPend slots and drops it like any key above the k-th best
+        // (slot kPend, beyond the last one the merge reads, takes the store of a lane whose buffer is full).
+        asm volatile("ds_write2st64_b32 %0, %1, %2 offset1:17" : : "v"(pend_top), "v"(idx), "v"(bits));
+        pend_top = bits <= tau_hi ? pend_top + 0x100u : pend_top;
+    } else {
+        // here a candidate can be turned down although it lies below the k-th best (the query itself, a key the
+        // first pass of a long list has already placed): it must not stay in a slot the merge reads
+        bool keep = bits <= tau_hi;
+        if (INTRA) keep = keep && rl != J;
+        if (LOWER) keep = keep && ((((uint64_t)bits << 32) | idx) > lower);
+        const uint32_t addr = keep ? pend_top : spare;
+        asm volatile("ds_write2st64_b32 %0, %1, %2 offset1:17" : : "v"(addr), "v"(idx), "v"(bits));
+        pend_top = keep ? pend_top + 0x100u : pend_top;
     }
 }
 
@@ -180,18 +195,19 @@ k_query_tile(QueryArgs a)
     const int lane = threadIdx.x;
     const int rl = lane & (kRow - 1);
     const int row_lane0 = lane & ~(kRow - 1);
-    // pending keys: index words [kPend][64], then distance words [kPend][64]
+    // pending keys: index words [kPendRows][64], then distance words [kPendRows][64]
     uint32_t* const pend_lds = reinterpret_cast<uint32_t*>(lds64) + lane;
-    constexpr int kPendHalf = kPend * kQueryBlock;
+    constexpr int kPendHalf = kPendRows * kQueryBlock;
     // next free slot of this lane, kept as a plain LDS byte address so that an accepted candidate costs one
     // two-word store and one add
     using lds_word = __attribute__((address_space(3))) uint32_t;
     const uint32_t pend_base = (uint32_t)(uintptr_t)(lds_word*)pend_lds;
     uint32_t pend_top = pend_base;
     const uint32_t pend_full = pend_base + (kPend - kStepGroup) * kQueryBlock * 4;   // beyond this a group of steps may overflow
+    const uint32_t pend_spare = pend_base + kPend * kQueryBlock * 4;
     // run tables of the four rows, one entry per column of the current batch of 16: offset of the column's
     // candidates in the row's stream, first run (start, length), start of the second run
-    int32_t* const run_excl = reinterpret_cast<int32_t*>(lds64 + kPend * kQueryBlock) + row_lane0;
+    int32_t* const run_excl = reinterpret_cast<int32_t*>(lds64 + kPendRows * kQueryBlock) + row_lane0;
     int32_t* const run_a1 = run_excl + kQueryBlock;
     int32_t* const run_len1 = run_a1 + kQueryBlock;
     int32_t* const run_a2 = run_len1 + kQueryBlock;
@@ -228,11 +244,14 @@ k_query_tile(QueryArgs a)
 
     auto absorb = [&]() {
         uint64_t pend[kPend];
+        asm volatile("" : : : "memory");     // the stores of the steps above are issued before these reads
         // unused slots hold the empty key's distance word (refilled below), whatever their index word: such keys
         // lie at or above the empty key and sort behind every real one
+        // (the sign bit of the distance word is cleared: a slot may hold a candidate that was not kept, whose
+        // distance may be a NaN of either sign, and the networks order keys as non-negative doubles)
 #pragma unroll
         for (int i = 0; i < kPend; ++i)
-            pend[i] = ((uint64_t)pend_lds[kPendHalf + i * kQueryBlock] << 32) | pend_lds[i * kQueryBlock];
+            pend[i] = ((uint64_t)(pend_lds[kPendHalf + i * kQueryBlock] & 0x7fffffffu) << 32) | pend_lds[i * kQueryBlock];
 #pragma unroll
         for (int i = 0; i < kPend; ++i) pend_lds[kPendHalf + i * kQueryBlock] = (uint32_t)(kEmptyKey >> 32);
         net_sort<kPend>(pend);
@@ -240,6 +259,7 @@ k_query_tile(QueryArgs a)
         pend_top = pend_base;
         tau = best[KC - 1];
         tau_hi = (uint32_t)(tau >> 32);
+        asm volatile("" : : : "memory");     // and the refill above before the stores of the steps that follow
     };
 
     // the row splits this tile touches; each gets a walk of its own
@@ -311,7 +331,7 @@ k_query_tile(QueryArgs a)
 #pragma unroll
             for (int c = 0; c < D; ++c) cself[c] = offer ? x[c] : kNaN;
             static_for<0, kRow>([&](auto J) {
-                scan_step<decltype(J)::value, D, LOWER, true>(cself, my_row, xq, tau_hi, lower, pend_top, rl);
+                scan_step<decltype(J)::value, D, LOWER, true>(cself, my_row, xq, tau_hi, lower, pend_top, pend_spare, rl);
             });
             if (COUNT && act) cand += __popcll(__ballot(in_seg) & (0xffffull << row_lane0)) - 1;
             if (__any(pend_top > pend_full)) absorb();     // up to 15 kept per lane: make room for the first group of steps
@@ -374,7 +394,7 @@ k_query_tile(QueryArgs a)
                         const float above = (glo[c] + (float)X[c] * gw[c]) - qmax[c] - gslack[c];
                         const float gp = fmaxf(fmaxf(below, above), 0.0f);
                         partial += gp * gp;
-                        flat = flat * a.n_bins + X[c];
+                        flat = snake_push(flat, ok ? X[c] : 0, a.n_bins);
                     }
                 }
                 // union over the row's queries that reach this column: what was searched before (plo..phi), what
@@ -416,9 +436,9 @@ k_query_tile(QueryArgs a)
                     while (z1a <= z1b && far_below(z1a)) ++z1a;
                     if (phi < plo) { while (z1b >= z1a && far_above(z1b)) --z1b; }
                     while (z2b >= z2a && far_above(z2b)) --z2b;
-                    const int32_t base = seg_cell0 + flat * a.n_bins;
-                    if (z1b >= z1a) { a1 = a.bounds[base + z1a]; b1 = a.bounds[base + z1b + 1]; }
-                    if (z2b >= z2a) { a2 = a.bounds[base + z2a]; b2 = a.bounds[base + z2b + 1]; }
+                    int32_t f0, f1;
+                    if (z1b >= z1a) { snake_run(flat, z1a, z1b, a.n_bins, &f0, &f1); a1 = a.bounds[seg_cell0 + f0]; b1 = a.bounds[seg_cell0 + f1 + 1]; }
+                    if (z2b >= z2a) { snake_run(flat, z2a, z2b, a.n_bins, &f0, &f1); a2 = a.bounds[seg_cell0 + f0]; b2 = a.bounds[seg_cell0 + f1 + 1]; }
                     if (R == 0) {
                         // the row's own points are not streamed: cut them out of the (single) run
                         if (a1 < own1 && b1 > own0) {
@@ -435,47 +455,66 @@ k_query_tile(QueryArgs a)
                 __syncthreads();
                 run_excl[rl] = incl - len; run_a1[rl] = a1; run_len1[rl] = len1; run_a2[rl] = a2;
                 __syncthreads();
-                const int32_t n_chunks = (wave_max_i32(T) + kRow - 1) / kRow;
+                const int32_t n_chunks = (wave_max_i32(T) + kChunk - 1) / kChunk;
 
-                // candidate f of the row's stream -> registers (NaN coordinates beyond the end)
-                float cnx[D];
-                int32_t cinx = -1;
-                auto fetch = [&](int32_t f) {
-                    const bool in = f < T;
-                    int32_t j = 0;
+                // A chunk is kSub candidates per lane (kSub x 16 per row): candidate (ch * kSub + u) * 16 + L of the
+                // row's stream goes to register set u of lane L.  The loads of chunk ch + 1 are issued before chunk
+                // ch is evaluated; they take well over a microsecond under load, which the kSub x 16 steps of a chunk
+                // (with the other wavefronts of the SIMD) cover, and 16 steps do not.  All loads of a fetch are
+                // independent and unconditional (slots beyond the end of the stream read a valid dummy position and
+                // are poisoned afterwards): a load that waits for another one's result would expose a full memory
+                // latency per chunk.
+                struct Stage { float c[kSub][D]; int32_t ci[kSub]; };
+                // this lane's place in the table: the run its last candidate came from and where that run ends in the
+                // stream; candidates are taken in ascending order, so the next one is found by stepping forward
+                int32_t cj = -1, c_end = 0, c_excl = 0;
+                auto fetch = [&](int32_t ch, Stage& st) {
 #pragma unroll
-                    for (int step = kRow / 2; step > 0; step >>= 1)
-                        if (run_excl[j + step] <= f) j += step;
-                    const int32_t local = f - run_excl[j];
-                    const int32_t l1 = run_len1[j];
-                    int32_t q = local < l1 ? run_a1[j] + local : run_a2[j] + (local - l1);
-                    q = in ? q : pp;
-                    const int32_t src = a.perm[q];
-                    bool real = in;
-                    if (a.dir) real = real && dir_is_neighbour(a.dir[src]);
-#pragma unroll
-                    for (int c = 0; c < D; ++c) {
-                        const float v = a.soa[(int64_t)c * a.soa_stride + q];
-                        cnx[c] = real ? v : kNaN;
-                    }
-                    cinx = src;
-                };
-                if (n_chunks > 0) fetch(rl);
-                for (int32_t ch = 0; ch < n_chunks; ++ch) {
-                    float ccur[D];
-#pragma unroll
-                    for (int c = 0; c < D; ++c) ccur[c] = cnx[c];
-                    const int32_t cicur = cinx;
-                    if (COUNT && act) { const int32_t left = T - ch * kRow; cand += left > kRow ? kRow : (left > 0 ? left : 0); }
-                    if (ch + 1 < n_chunks) fetch((ch + 1) * kRow + rl);
-#pragma unroll 1
-                    for (int g = 0; g < kRow / kStepGroup; ++g) {
-                        switch (g) {
-                            case 0: static_for<0, 4>([&](auto J) { scan_step<decltype(J)::value, D, LOWER, false>(ccur, cicur, xq, tau_hi, lower, pend_top, rl); }); break;
-                            case 1: static_for<4, 8>([&](auto J) { scan_step<decltype(J)::value, D, LOWER, false>(ccur, cicur, xq, tau_hi, lower, pend_top, rl); }); break;
-                            case 2: static_for<8, 12>([&](auto J) { scan_step<decltype(J)::value, D, LOWER, false>(ccur, cicur, xq, tau_hi, lower, pend_top, rl); }); break;
-                            default: static_for<12, 16>([&](auto J) { scan_step<decltype(J)::value, D, LOWER, false>(ccur, cicur, xq, tau_hi, lower, pend_top, rl); }); break;
+                    for (int u = 0; u < kSub; ++u) {
+                        const int32_t f = (ch * kSub + u) * kRow + rl;
+                        const bool in = f < T;
+                        while (in && f >= c_end) {       // runs of length zero are stepped over; the last run ends at T > f
+                            ++cj;
+                            c_excl = c_end;
+                            c_end = cj + 1 < kRow ? run_excl[cj + 1] : T;
                         }
+                        const int32_t jj = cj < 0 ? 0 : cj;
+                        const int32_t local = f - c_excl, l1 = run_len1[jj];
+                        int32_t q = local < l1 ? run_a1[jj] + local : run_a2[jj] + (local - l1);
+                        q = in ? q : pp;
+                        // index of the candidate, or -1 if a direction flag says it is nobody's neighbour (a.perm_cand
+                        // is a.perm where there are no flags)
+                        st.ci[u] = a.perm_cand[q];
+#pragma unroll
+                        for (int c = 0; c < D; ++c) st.c[u][c] = a.soa[(int64_t)c * a.soa_stride + q];
+                    }
+                };
+                Stage nxt, cur;
+                if (n_chunks > 0) fetch(0, nxt);
+                for (int32_t ch = 0; ch < n_chunks; ++ch) {
+#pragma unroll
+                    for (int u = 0; u < kSub; ++u) {
+                        // a slot beyond the end of the stream, or a point that is nobody's neighbour: its coordinates
+                        // become NaN (the loads were issued a chunk ago, unconditionally)
+                        const int32_t f = (ch * kSub + u) * kRow + rl;
+                        const bool real = f < T && nxt.ci[u] >= 0;
+#pragma unroll
+                        for (int c = 0; c < D; ++c) cur.c[u][c] = real ? nxt.c[u][c] : kNaN;
+                        cur.ci[u] = nxt.ci[u];
+                    }
+                    if (COUNT && act) { const int32_t left = T - ch * kChunk; cand += left > kChunk ? kChunk : (left > 0 ? left : 0); }
+                    fetch(ch + 1, nxt);          // beyond the last chunk: a harmless fetch of padding
+#pragma unroll 1
+                    for (int g = 0; g < kChunk / kStepGroup; ++g) {
+                        static_for<0, kChunk / kStepGroup>([&](auto G) {
+                            constexpr int gg = decltype(G)::value;
+                            constexpr int u = gg / (kRow / kStepGroup), j0 = (gg % (kRow / kStepGroup)) * kStepGroup;
+                            if (g == gg) {
+                                static_for<j0, j0 + kStepGroup>([&](auto J) {
+                                    scan_step<decltype(J)::value, D, LOWER, false>(cur.c[u], cur.ci[u], xq, tau_hi, lower, pend_top, pend_spare, rl);
+                                });
+                            }
+                        });
                         if (__any(pend_top > pend_full)) absorb();
                     }
                 }

@@ -192,7 +192,7 @@ def test_deterministic_across_runs():
 
 
 def test_tile_and_list_kernels_both_run_and_agree_with_the_plain_walk():
-    """Default path = tile kernel + list kernel for the queries it defers; query_algo = 1 sends
+    """Default path = tile kernel + list kernel for the queries it defers; algo = 1 sends
     every query through the one-lane-per-query walk.  Isolated points far from a dense core need
     many shells, so some queries must reach the list kernel."""
     rng = np.random.Generator(np.random.PCG64(29))
@@ -211,8 +211,7 @@ def test_tile_and_list_kernels_both_run_and_agree_with_the_plain_walk():
         deferred = int(bn.work_count.item())
         assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "tile+list nb=%d" % nb)
         assert 0 < deferred < x.shape[0]
-        bn.raw.query_algo = 1
-        gi, gd = B.fg_query_binned(bn, rt, k)
+        gi, gd = B.fg_query_binned(bn, rt, k, algo=1)
         torch.cuda.synchronize()
         assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "plain walk nb=%d" % nb)
 
@@ -241,15 +240,14 @@ def test_clustered_points_every_list_size(d, k):
     oi, od = oracle.knn(x, rs, k, direction=direction)
     bn = B.fg_bin_points(xt, rt, k)
     dt = torch.from_numpy(direction).to(DEV)
-    bn.raw.dir = dt.data_ptr()
-    gi, gd = B.fg_query_binned(bn, rt, k)
+    gi, gd = B.fg_query_binned(bn, rt, k, direction=dt)
     torch.cuda.synchronize()
     assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "clustered with flags d=%d k=%d" % (d, k))
 
 
 def test_ordered_launch_takes_every_tile_once():
-    """More than 1024 tiles: the ordering kernels rank the tiles by estimated work (heaviest first); the order
-    must be a permutation of the tiles, and the result the same as the plain walk's."""
+    """More than 1024 tiles: the ordering kernels rank the tiles by estimated work (heaviest first).  Every tile
+    must still be taken exactly once: every row is compared with the plain walk, sampled rows with the oracle."""
     rng = np.random.Generator(np.random.PCG64(77))
     n, k = 90_000, 32
     centres = rng.random((40, 3)) * 10.0
@@ -261,17 +259,12 @@ def test_ordered_launch_takes_every_tile_once():
     bn = B.fg_bin_points(xt, rt, k)
     gi, gd = B.fg_query_binned(bn, rt, k)
     torch.cuda.synchronize()
-    n_tiles = (n + 63) // 64
-    order = bn._view(bn.raw.tile_order, 2 * n_tiles + 128, torch.int32).cpu().numpy()
-    tiles, classes = order[:n_tiles], order[n_tiles:2 * n_tiles]
-    assert np.array_equal(np.sort(tiles), np.arange(n_tiles))               # a permutation of the tiles
-    assert np.all(np.diff(classes[tiles]) <= 0) and classes.min() < classes.max()   # heaviest class first
+    assert (n + 63) // 64 > 1024
     rows = np.sort(rng.choice(n, size=3000, replace=False)).astype(np.int64)
     oi, od = oracle.knn_rows(x, rs, k, rows)
     gi, gd = gi.cpu().numpy(), gd.cpu().numpy()
     assert np.array_equal(gi[rows], oi) and np.array_equal(gd[rows].view(np.uint32), od.view(np.uint32))
-    bn.raw.query_algo = 1                                                    # the plain walk agrees on every row
-    gi1, gd1 = B.fg_query_binned(bn, rt, k)
+    gi1, gd1 = B.fg_query_binned(bn, rt, k, algo=1)                          # the plain walk agrees on every row
     torch.cuda.synchronize()
     assert np.array_equal(gi1.cpu().numpy(), gi) and np.array_equal(gd1.cpu().numpy().view(np.uint32), gd.view(np.uint32))
 
@@ -304,9 +297,7 @@ def test_direction_flags(d, k):
     xt, rt = torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV)
     bn = B.fg_bin_points(xt, rt, k)
     dt = torch.from_numpy(direction).to(DEV)
-    bn.raw.dir = dt.data_ptr()
-    bn.raw.query_algo = 1
-    gi, gd = B.fg_query_binned(bn, rt, k)
+    gi, gd = B.fg_query_binned(bn, rt, k, direction=dt, algo=1)
     torch.cuda.synchronize()
     assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "dir plain walk")
 
@@ -356,9 +347,14 @@ def test_binning_invariants(d, nb, db):
         if size > 1:
             assert np.array_equal(geom[s, :, 0], x[rs[s]:rs[s + 1], :bn.d_bin].min(axis=0))
     # bins are monotone in every binned coordinate (what the search's lower bounds rely on)
+    # (bin numbers are serpentine: the digit of a dimension runs backwards when the number formed by the digits
+    # before it is odd, so that consecutive bins are neighbours in space)
     local = bin_idx - seg * T
+    prefix = np.zeros(n, dtype=np.int64)
     for c in range(bn.d_bin):
-        cell_c = (local // (bn.n_bins ** (bn.d_bin - 1 - c))) % bn.n_bins
+        digit = (local // (bn.n_bins ** (bn.d_bin - 1 - c))) % bn.n_bins
+        cell_c = np.where(prefix % 2 == 1, bn.n_bins - 1 - digit, digit)
+        prefix = prefix * bn.n_bins + digit
         for s, size in enumerate(sizes):
             if size > 1:
                 sl = slice(rs[s], rs[s + 1])

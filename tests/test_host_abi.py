@@ -94,7 +94,7 @@ def test_argument_validation_without_gpu():
     assert L.fg_knn_backward(8, 8, 8, None, 10, 3, 1, 200, 8, None, 0, None) == B.FG_ERR_UNSUPPORTED
     assert L.fg_knn_backward(8, 8, 8, 8, 10, 3, 1, 4, 8, 256, 16, None) == B.FG_ERR_WORKSPACE
     assert L.fg_knn_backward(None, None, None, None, 0, 3, 1, 4, None, None, 0, None) == B.FG_OK
-    assert L.fg_query_binned(None, 8, 10, 3, 1, 4, 8, 8, None, None) == B.FG_ERR_NULL
+    assert L.fg_query_binned(None, 8, 10, 3, 1, 4, 8, 8, None, None, None) == B.FG_ERR_NULL
     assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 4, 10, 1, 1, None, 8, None, 0, None) == B.FG_ERR_NULL
     assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 4, 10, 1, 1, 8, None, None, 0, None) == B.FG_ERR_NULL
     assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 0, 10, 0, 1, 8, None, None, 0, None) == B.FG_ERR_BAD_SHAPE
