@@ -72,10 +72,9 @@ fg_status fg_workspace_size(int64_t n, int32_t d, int32_t n_segments, int32_t k,
 
 /* Result of the binning stage: device pointers into the caller's workspace. */
 typedef struct {
-    const int32_t* bin_idx;    /* [n]  bin number of each point, ORIGINAL order; segment s owns bins [s*T, (s+1)*T).
-                                  Inside a segment bins are numbered in serpentine order over the grid: the digit of
-                                  binning dimension c (most significant first) runs backwards when the number formed by
-                                  the digits before it is odd, so that consecutive bin numbers are neighbours in space */
+    const int32_t* bin_idx;    /* [n]  flat bin of each point, ORIGINAL order; segment s owns bins [s*T, (s+1)*T); inside
+                                  a segment the bins are numbered row-major over the grid, last binning dimension
+                                  fastest (the flattening of Algorithm 1) */
     const int32_t* perm;       /* [n]  sorted position -> original row index */
     const int32_t* bin_bounds; /* [n_segments*T + 1] exclusive prefix of bin populations: bin b holds
                                   sorted positions [bin_bounds[b], bin_bounds[b+1]) */
@@ -95,16 +94,16 @@ typedef struct {
 typedef struct {
     const int32_t* dir;        /* [n] direction flags in ORIGINAL row order (see fg_binned_select_knn_dir), or NULL */
     int32_t algo;              /* 0: tile kernel + list kernel (default); 1: the one-lane-per-query shell walk for
-                                  every query (slower; kept for cross-checking) */
+                                  every query (slower; kept for cross-checking); 2: as 0, with the tile kernel's
+                                  flattened scan on every tile instead of the uneven ones only (for tests) */
     int32_t defer_lanes;       /* after shell 1 a wavefront of the tile kernel goes on to the next shell only while
                                   more than this many of its 64 queries are unfinished, the rest go to the list
                                   kernel; 0..64, negative: the default */
 } fg_query_options;
 
 /* Spatial partition + counting sort (Section 3, second paragraph: bins per row split, points ordered by bin,
- * cumulative bin boundaries; Algorithm 2 inputs binIdx, binBounds, binCounts, binWidths).  The paper numbers
- * bins row-major (Algorithm 1); here the numbering is serpentine (see bin_idx), which keeps runs of the last
- * dimension contiguous and makes consecutive points in bin order neighbours in space.
+ * cumulative bin boundaries; Algorithm 2 inputs binIdx, binBounds, binCounts, binWidths; bins numbered
+ * row-major as in Algorithm 1).
  * Per row split: bounding box over the first d_bin coordinates; bin of a point in dimension c =
  * min(n_bins-1, floor((x_c - lo_c) * n_bins / (hi_c - lo_c))), 0 if hi_c == lo_c.
  *   coords      [n][d] row-major float32

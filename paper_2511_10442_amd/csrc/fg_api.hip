@@ -287,15 +287,8 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
     a.n_bins = view->n_bins; a.cells_per_segment = (int32_t)view->cells_per_segment;
     a.work_list = (int32_t*)(sc + S.work_list); a.work_count = (int32_t*)(sc + S.work_count);
     a.bin_idx = view->bin_idx; a.tile_order = (int32_t*)(sc + S.tile_order);
-    a.algo = (options && options->algo == 1) ? 1 : 0;
+    a.algo = (options && (options->algo == 1 || options->algo == 2)) ? options->algo : 0;
     a.defer_lanes = defer > 64 ? 64 : defer;
-    a.perm_cand = view->perm;
-    if (dir) {
-        // candidates that a flag excludes: their entry of the permutation the tile kernel reads becomes -1
-        int32_t* masked = (int32_t*)(sc + S.rank);
-        if (launch_mask_perm(view->perm, dir, (int32_t)n, masked, (hipStream_t)stream) != hipSuccess) return FG_ERR_LAUNCH;
-        a.perm_cand = masked;
-    }
     hipError_t e = launch_query(a, d, view->d_bin, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }

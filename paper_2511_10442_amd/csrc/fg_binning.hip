@@ -200,9 +200,9 @@ k_assign(const float* __restrict__ coords, const int32_t* __restrict__ row_split
             cell[c] = cell_of(p[c], r.lo, r.inv_w, n_bins);
         }
         int32_t f = 0;
-        if (morton_bits == 0) {                 // serpentine order, last dimension fastest (what the query kernels expect)
+        if (morton_bits == 0) {                 // row-major, last dimension fastest (what the query kernels expect)
 #pragma unroll
-            for (int c = 0; c < DB; ++c) f = snake_push(f, cell[c], n_bins);
+            for (int c = 0; c < DB; ++c) f = f * n_bins + cell[c];
         } else {                                // bit-interleaved: consecutive bins form compact blocks in space
             for (int b = 0; b < morton_bits; ++b) {
 #pragma unroll
@@ -349,21 +349,6 @@ k_scatter(const float* __restrict__ coords, int32_t n, const int32_t* __restrict
 #pragma unroll
         for (int c = 0; c < D; ++c) soa[(int64_t)c * soa_stride + pos] = p[c];
     }
-}
-
-__global__ void __launch_bounds__(kBlock)
-k_mask_perm(const int32_t* __restrict__ perm, const int32_t* __restrict__ dir, int32_t n, int32_t* __restrict__ out)
-{
-    const int64_t q = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (q >= n) return;
-    const int32_t src = perm[q];
-    out[q] = dir_is_neighbour(dir[src]) ? src : -1;
-}
-
-hipError_t launch_mask_perm(const int32_t* perm, const int32_t* dir, int32_t n, int32_t* out, hipStream_t stream)
-{
-    hipLaunchKernelGGL(k_mask_perm, dim3((unsigned)(((int64_t)n + kBlock - 1) / kBlock)), dim3(kBlock), 0, stream, perm, dir, n, out);
-    return hipGetLastError();
 }
 
 template <int DB>

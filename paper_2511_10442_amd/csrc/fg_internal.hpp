@@ -14,7 +14,6 @@ constexpr int kKeyStride = 16;   // words between two bounding-box keys: one 64-
 struct QueryArgs {
     const float* soa;          // [d][soa_stride] bin-ordered coordinates
     const int32_t* perm;       // [n] sorted position -> original row
-    const int32_t* perm_cand;  // [n] the same, but -1 where a direction flag says the point is nobody's neighbour (= perm without flags)
     const int32_t* bounds;     // [S*T+1]
     const float* geom;         // [S][d_bin][4]
     const int32_t* row_splits; // [S+1]
@@ -34,7 +33,7 @@ struct QueryArgs {
     int32_t k_list;            // tile + list kernels: neighbours this pass finds (1..64, or 0 for K = 1); they go to row slots slot0+1 .. slot0+k_list
     int32_t n_bins;
     int32_t cells_per_segment;
-    int32_t algo;              // 0: tile kernel + list kernel, 1: one lane per query for everything
+    int32_t algo;              // 0: tile kernel + list kernel, 1: one lane per query for everything, 2: as 0 with the flattened scan on every tile
     int32_t defer_lanes;       // tile kernel: go on past shell 1 only while more lanes than this are unfinished
 };
 
@@ -49,9 +48,6 @@ hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_
                                                  only perm is written, plus for d = 3 a copy of coords in the original
                                                  order padded to float4 in place of the SoA */,
                           hipStream_t stream);
-
-// out[q] = perm[q] if the point may be a neighbour (direction flag), else -1
-hipError_t launch_mask_perm(const int32_t* perm, const int32_t* dir, int32_t n, int32_t* out, hipStream_t stream);
 
 // d = 2..10, d_bin = 2..min(d,5)
 hipError_t launch_query(const QueryArgs& a, int32_t d, int32_t d_bin, hipStream_t stream);
@@ -98,40 +94,6 @@ __device__ __forceinline__ int32_t cell_of(float x, float lo, float inv_w, int32
     int32_t c = (int32_t)floorf(t);
     c = c < 0 ? 0 : c;
     return c > n_bins - 1 ? n_bins - 1 : c;
-}
-
-// ---- serpentine bin order ------------------------------------------------------------------------------
-// Bins are numbered in boustrophedon order over the grid: the digit of binning dimension c runs forwards or
-// backwards depending on the parity of the number formed by the digits before it, so that two consecutive bins
-// are always neighbours in space (they differ by one step in exactly one dimension).  Points sorted by bin are
-// then spatially coherent across the end of a run of the last dimension, which a plain row-major order is not
-// (there the next bin after the top of one run is the bottom of the next).  The bins of one column (fixed first
-// DB-1 digits) are still consecutive numbers, so a range of last-dimension bins is still one run of points.
-// snake_push: appends bin coordinate `cell` (0 <= cell < n_bins) of the next dimension to the prefix number f.
-__host__ __device__ __forceinline__ int32_t snake_push(int32_t f, int32_t cell, int32_t n_bins)
-{
-    return f * n_bins + ((f & 1) ? n_bins - 1 - cell : cell);
-}
-// first and last bin number (inclusive) of the last-dimension bins za..zb of the column with prefix number f
-__host__ __device__ __forceinline__ void snake_run(int32_t f, int32_t za, int32_t zb, int32_t n_bins, int32_t* first, int32_t* last)
-{
-    const int32_t base = f * n_bins;
-    if (f & 1) { *first = base + n_bins - 1 - zb; *last = base + n_bins - 1 - za; }
-    else { *first = base + za; *last = base + zb; }
-}
-// bin coordinates of bin number `local` (inside its row split)
-template <int DB>
-__host__ __device__ __forceinline__ void snake_cells(int32_t local, int32_t n_bins, int32_t (&cell)[DB])
-{
-    int32_t digit[DB];
-#pragma unroll
-    for (int c = DB - 1; c >= 0; --c) { digit[c] = local % n_bins; local /= n_bins; }
-    int32_t f = 0;
-#pragma unroll
-    for (int c = 0; c < DB; ++c) {
-        cell[c] = (f & 1) ? n_bins - 1 - digit[c] : digit[c];
-        f = f * n_bins + digit[c];
-    }
 }
 
 }  // namespace fg

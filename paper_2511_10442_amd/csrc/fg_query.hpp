@@ -23,6 +23,7 @@
 namespace fg {
 
 constexpr int kQueryBlock = 64;                    // one wavefront per workgroup
+constexpr int kStageChunk = 256;                   // most points staged through LDS per chunk (tile kernel)
 constexpr float kBoundShrink = 0.99999618530273f;  // 1 - 2^-18: covers fp32 rounding of d2 and of the bound
 
 // Per-lane geometry of one query: its coordinates, its bin, its row split's grid, and the
@@ -183,25 +184,22 @@ struct ShellSearch : LaneGeom<D, DB> {
                 float p2 = partial + g * g;
                 if (cannot_improve(p2)) continue;
                 bool on = surf || o == r || o == -r;
-                visit<LVL + 1>(r, snake_push(flat, c0 + o, n_bins), p2, on);
+                visit<LVL + 1>(r, flat * n_bins + c0 + o, p2, on);
             }
         } else {
-            int32_t b0, b1;
+            const int32_t row = seg_cell0 + flat * n_bins;
             if (surf) {   // the whole run of the last dimension belongs to this shell
                 int32_t za = c0 - r < 0 ? 0 : c0 - r;
                 int32_t zb = c0 + r > neff[LVL] - 1 ? neff[LVL] - 1 : c0 + r;
-                snake_run(flat, za, zb, n_bins, &b0, &b1);
-                scan_points(bounds[seg_cell0 + b0], bounds[seg_cell0 + b1 + 1]);
+                scan_points(bounds[row + za], bounds[row + zb + 1]);
             } else {      // only the two end bins of the run are on the surface
                 if (c0 - r >= 0) {
                     float g = gap(LVL, c0 - r, -r);
-                    snake_run(flat, c0 - r, c0 - r, n_bins, &b0, &b1);
-                    if (!cannot_improve(partial + g * g)) scan_points(bounds[seg_cell0 + b0], bounds[seg_cell0 + b1 + 1]);
+                    if (!cannot_improve(partial + g * g)) scan_points(bounds[row + c0 - r], bounds[row + c0 - r + 1]);
                 }
                 if (c0 + r <= neff[LVL] - 1) {
                     float g = gap(LVL, c0 + r, r);
-                    snake_run(flat, c0 + r, c0 + r, n_bins, &b0, &b1);
-                    if (!cannot_improve(partial + g * g)) scan_points(bounds[seg_cell0 + b0], bounds[seg_cell0 + b1 + 1]);
+                    if (!cannot_improve(partial + g * g)) scan_points(bounds[row + c0 + r], bounds[row + c0 + r + 1]);
                 }
             }
         }

@@ -12,7 +12,8 @@ namespace fg {
 // sets the kernel's end: measured on the 1M-point clustered workload the tile kernel took 1.2 ms for 0.73 ms of
 // evenly spread work, the last third of it with most of the chip idle.  The tiles are therefore ranked by an
 // estimate of their work, in 64 classes of half a power of two, heaviest class first.
-// tile_order: [0, T) the order, [T, 2T) class of each tile, [2T, 2T+64) class histogram, [2T+64, 2T+128) cursors.
+// tile_order: [0, T) the order, [T, 2T) class of each tile (bit 6: uneven, see k_tile_work), [2T, 2T+64) class
+// histogram, [2T+64, 2T+128) cursors.
 constexpr int kTileClasses = 64;
 
 static __global__ void k_reset_query_scratch(int32_t* work_count, int32_t* tile_counters)
@@ -37,6 +38,8 @@ constexpr int kTilesPerWave = 16;
 // (every ninth: consecutive queries mostly share their bins), 8 tiles per wavefront at a time: with all 64 the
 // gathers of the bin boundaries made this kernel cost 73 us per million points.
 constexpr int kTileSamples = 8;
+constexpr int kFlatLaneUsePct = 60;   // below this estimated lane use (per cent) a tile takes the flattened scan
+static_assert(kTileClasses == (1 << kTileFlatBit), "the flag sits above the class bits");
 
 // maximum / sum over each aligned group of 8 lanes, returned in all 8 (DPP: swap inside pairs, swap pairs, mirror the half row)
 __device__ __forceinline__ int32_t oct_max_i32(int32_t v)
@@ -73,11 +76,12 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
         int32_t cc[DB], seg_cell0 = 0;
         {
             const int32_t b = live ? a.bin_idx[a.perm[p]] : 0;
-            const int32_t r = b % a.cells_per_segment;
+            int32_t r = b % a.cells_per_segment;
             seg_cell0 = b - r;
-            snake_cells<DB>(r, a.n_bins, cc);
+#pragma unroll
+            for (int c = DB - 1; c >= 0; --c) { cc[c] = r % a.n_bins; r /= a.n_bins; }
         }
-        int32_t work = 0, around = 0;
+        int32_t work = 0, around = 0, longest = 0, total = 0;
         for (int32_t col = 0; col < ncols; ++col) {
             int32_t rem = col, flat = 0;
             bool ok = live;
@@ -86,18 +90,20 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
                 const int32_t j = cc[c] + rem % 3 - 1;
                 rem /= 3;
                 ok = ok && j >= 0 && j < a.n_bins;
-                flat = snake_push(flat, ok ? j : 0, a.n_bins);
+                flat = flat * a.n_bins + j;
             }
             int32_t len = 0;
             if (ok) {
                 const int32_t cz = cc[DB - 1];
                 const int32_t za = cz > 0 ? cz - 1 : 0, zb = cz < a.n_bins - 1 ? cz + 1 : a.n_bins - 1;
-                int32_t f0, f1;
-                snake_run(flat, za, zb, a.n_bins, &f0, &f1);
-                len = a.bounds[seg_cell0 + f1 + 1] - a.bounds[seg_cell0 + f0];
+                const int32_t row = seg_cell0 + flat * a.n_bins;
+                len = a.bounds[row + zb + 1] - a.bounds[row + za];
             }
             around += len;
-            work += oct_max_i32(len) >> 2;         // in units of four candidates; keeps the sum small
+            const int32_t col_max = oct_max_i32(len);
+            work += col_max >> 2;                  // in passes of four; keeps the sum small
+            longest += col_max;
+            total += oct_sum_i32(len);
         }
         // A query with few points around it will not be certified after shell 1 (the k-th neighbour of a query at
         // the centre of its bin lies inside the inscribed ball of the 3-bin cube, about a sixth of its volume, only
@@ -117,22 +123,26 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
                     const int32_t j = cc[c] + rem % 5 - 2;
                     rem /= 5;
                     ok = ok && j >= 0 && j < a.n_bins;
-                    flat = snake_push(flat, ok ? j : 0, a.n_bins);
+                    flat = flat * a.n_bins + j;
                 }
                 int32_t len = 0;
                 if (ok) {
                     const int32_t cz = cc[DB - 1];
                     const int32_t za = cz > 1 ? cz - 2 : 0, zb = cz < a.n_bins - 2 ? cz + 2 : a.n_bins - 1;
-                    int32_t f0, f1;
-                    snake_run(flat, za, zb, a.n_bins, &f0, &f1);
-                    len = a.bounds[seg_cell0 + f1 + 1] - a.bounds[seg_cell0 + f0];
+                    const int32_t row = seg_cell0 + flat * a.n_bins;
+                    len = a.bounds[row + zb + 1] - a.bounds[row + za];
                 }
                 work += oct_max_i32(len) >> 2;
             }
         }
         if (sample == 0 && t < n_tiles) {
             const int32_t cls = tile_class(work);
-            a.tile_order[n_tiles + t] = cls;
+            // Uneven tile: over these columns its queries' runs average less than kFlatLaneUsePct of the longest
+            // one, so a direct scan (every column as long as its busiest lane) leaves most lanes idle and the
+            // flattened scan, at about twice the cost per pass, still comes out ahead.  Pruning, which this
+            // estimate does not see, only widens the spread.
+            const bool uneven = total * 100 < longest * kTileSamples * kFlatLaneUsePct;
+            a.tile_order[n_tiles + t] = cls | ((uneven ? 1 : 0) << kTileFlatBit);
             atomicAdd(&hist[cls], 1);
         }
     }
@@ -156,16 +166,18 @@ static __global__ void __launch_bounds__(256) k_tile_rank(int32_t* __restrict__ 
     }
     __syncthreads();
     const int32_t t = blockIdx.x * 256 + threadIdx.x;
-    int32_t cls = 0, mine = 0;
+    int32_t cls = 0, mine = 0, uneven = 0;
     if (t < n_tiles) {
-        cls = order[n_tiles + t] & (kTileClasses - 1);
+        const int32_t word = order[n_tiles + t];
+        cls = word & (kTileClasses - 1);
+        uneven = (word >> kTileFlatBit) & 1;
         mine = atomicAdd(&local[cls], 1);
     }
     __syncthreads();
     if (threadIdx.x < kTileClasses && local[threadIdx.x] > 0)
         local[threadIdx.x] = atomicAdd(&order[2 * n_tiles + kTileClasses + threadIdx.x], local[threadIdx.x]);
     __syncthreads();
-    if (t < n_tiles) order[first[cls] + local[cls] + mine] = t;
+    if (t < n_tiles) order[first[cls] + local[cls] + mine] = t | (uneven << kOrderFlagBit);
 }
 
 template <typename K>
@@ -191,13 +203,17 @@ static void launch_query_pass(const QueryArgs& a_in, hipStream_t stream)
     }
     const int32_t cap = a.k_list;
     if (cap <= 16) {
-        hipLaunchKernelGGL((k_query_tile<D, DB, 16, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), tile_lds_bytes<16>(), stream, a);
+        const size_t lds = tile_sorted_lds_bytes<16, D>();
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 16, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     } else if (cap <= 32) {
-        hipLaunchKernelGGL((k_query_tile<D, DB, 32, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), tile_lds_bytes<32>(), stream, a);
+        const size_t lds = tile_sorted_lds_bytes<32, D>();
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 32, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     } else if (cap <= 48) {
-        hipLaunchKernelGGL((k_query_tile<D, DB, 48, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), tile_lds_bytes<48>(), stream, a);
+        const size_t lds = tile_sorted_lds_bytes<48, D>();
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 48, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     } else {
-        hipLaunchKernelGGL((k_query_tile<D, DB, 64, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), tile_lds_bytes<64>(), stream, a);
+        const size_t lds = tile_sorted_lds_bytes<64, D>();
+        hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 64, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     }
     // one query per wavefront; four times the wave slots of the chip: the queries differ widely in cost, and with
     // more, shorter workgroups the hardware dispatcher evens them out (cursors in memory cost more than they gained)

@@ -16,10 +16,7 @@
 // A far-searching query therefore costs a few memory round trips per shell, not one per bin.
 // The tile kernel has already searched the first shells of every query it hands over: its list so
 // far sits in the query's output row and the first unsearched shell in slot 0 of the distance row,
-// so the search resumes there with a k-th best that already prunes most of the new shell.  The tile
-// kernel searches the union of what the 16 queries of a row need, so that list may hold points
-// from beyond the shells named as searched: a candidate whose key is already in the list it
-// started with is dropped (keys are unique per point).
+// so the search resumes there with a k-th best that already prunes most of the new shell.
 // A pass finds at most 64 neighbours; longer lists take two passes (see the launch code).
 #pragma once
 #include "fg_query.hpp"
@@ -69,7 +66,6 @@ __global__ void __launch_bounds__(kQueryBlock)
 k_query_list_wave(QueryArgs a)
 {
     __shared__ uint64_t pend[kListPend];
-    __shared__ uint64_t given[kQueryBlock];         // the list the query arrived with, ascending
     __shared__ int32_t seg_excl[kQueryBlock], seg_a1[kQueryBlock], seg_len1[kQueryBlock], seg_a2[kQueryBlock];
     const int lane = threadIdx.x;
     const int32_t count = *a.work_count;
@@ -97,8 +93,6 @@ k_query_list_wave(QueryArgs a)
         }
         const int32_t R0 = __float_as_int(od[0]);
         s.tau = __shfl(best, kQueryBlock - 1, 64);
-        given[lane] = best;
-        __syncthreads();
         int32_t npend = 0, cand = 0;
 
         auto absorb64 = [&]() {                     // merges pend[0..min(npend,64)) into the best list
@@ -144,14 +138,14 @@ k_query_list_wave(QueryArgs a)
                         ok = ok && j >= 0 && j < s.neff[c];
                         const float g = s.gap(c, j, o[c]);
                         partial += g * g;
-                        flat = snake_push(flat, ok ? j : 0, a.n_bins);
+                        flat = flat * a.n_bins + j;
                     }
                 }
                 ok = ok && !s.cannot_improve(partial);
                 int32_t a1 = 0, b1 = 0, a2 = 0, b2 = 0;
                 if (ok) {
                     const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
-                    int32_t f0, f1;
+                    const int32_t row = s.seg_cell0 + flat * a.n_bins;
                     if (surf) {
                         int32_t za = cz - R < 0 ? 0 : cz - R;
                         int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
@@ -165,19 +159,16 @@ k_query_list_wave(QueryArgs a)
                             if (!s.cannot_improve(partial + g * g)) break;
                             --zb;
                         }
-                        snake_run(flat, za, zb, a.n_bins, &f0, &f1);
-                        a1 = a.bounds[s.seg_cell0 + f0];
-                        b1 = a.bounds[s.seg_cell0 + f1 + 1];
+                        a1 = a.bounds[row + za];
+                        b1 = a.bounds[row + zb + 1];
                     } else {
                         if (cz - R >= 0) {
                             const float g = s.gap(DB - 1, cz - R, -R);
-                            snake_run(flat, cz - R, cz - R, a.n_bins, &f0, &f1);
-                            if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[s.seg_cell0 + f0]; b1 = a.bounds[s.seg_cell0 + f1 + 1]; }
+                            if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[row + cz - R]; b1 = a.bounds[row + cz - R + 1]; }
                         }
                         if (cz + R <= nz - 1) {
                             const float g = s.gap(DB - 1, cz + R, R);
-                            snake_run(flat, cz + R, cz + R, a.n_bins, &f0, &f1);
-                            if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[s.seg_cell0 + f0]; b2 = a.bounds[s.seg_cell0 + f1 + 1]; }
+                            if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[row + cz + R]; b2 = a.bounds[row + cz + R + 1]; }
                         }
                     }
                 }
@@ -209,14 +200,7 @@ k_query_list_wave(QueryArgs a)
                     const int32_t src = a.perm[q];
                     const bool live = in && q != p && !(a.dir && !dir_is_neighbour(a.dir[src]));
                     const uint64_t key = ((uint64_t)__float_as_uint(d2) << 32) | (uint32_t)src;
-                    bool acc = live && key < s.tau && (a.slot0 == 0 || key > lower);
-                    if (acc) {                      // already in the list it came with?
-                        int32_t lo = 0;
-#pragma unroll
-                        for (int step = kQueryBlock / 2; step > 0; step >>= 1)
-                            if (given[lo + step - 1] < key) lo += step;
-                        acc = given[lo] != key;
-                    }
+                    const bool acc = live && key < s.tau && (a.slot0 == 0 || key > lower);
                     if (COUNT) cand += __popcll(__ballot(live));
                     const uint64_t m = __ballot(acc);
                     if (m) {

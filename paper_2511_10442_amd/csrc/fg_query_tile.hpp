@@ -1,109 +1,53 @@
-// Main query kernel: one wavefront per tile of 64 consecutive bin-ordered queries, worked as four
-// sub-tiles of 16 queries (one DPP row each); the running best list of every lane is held SORTED
-// IN REGISTERS.
+// Main query kernel: one wavefront per tile of 64 consecutive bin-ordered queries, the running
+// best list of every lane held SORTED IN REGISTERS.
 //
 // What it computes is Algorithm 2 of the paper (Section 3): shells of bins of growing Chebyshev
 // radius around the query's bin, exact K-1 best others, stop once the k-th best is certified.
 // How it is laid out for CDNA4:
-//   * candidates are BROADCAST, not gathered: the 16 lanes of a row hold 16 candidates, one
-//     each, and in step J every lane of the row evaluates candidate J, read from lane J's
-//     registers by the DPP control row_newbcast:J folded into the subtraction itself.  A pair
-//     costs its 3d-1 float operations, one move for the candidate's index and one compare; no
-//     LDS read, no address arithmetic, every lane busy;
-//   * what a row scans is therefore the UNION of what its 16 queries need: per shell R and per
-//     column (a bin position in the first DB-1 binning dimensions; bins adjacent in the last one
-//     are adjacent in memory) the interval of last-dimension bins spanned by the cubes of
-//     radius R of the row's queries that reach the column.  The region scanned so far is, per
-//     column, one interval that only grows, so a shell adds at most two runs of sorted points
-//     per column, and no point is ever presented twice to a row;
-//   * the columns of a shell are worked out 16 at a time by the lanes of the row (one column per
-//     lane), their runs are laid end to end by a prefix sum, and lane L of the row fetches
-//     candidate 16 c + L of that stream for chunk c (binary search over the 16 runs; the loads
-//     of chunk c + 1 are issued before chunk c is evaluated);
+//   * the shell walk is wave-uniform: all 64 lanes step through the same column offsets
+//     (offsets in the first DB-1 binning dimensions) of the same shell together.  Queries of a
+//     tile are consecutive in bin order, so the bins they need for one column offset form one
+//     contiguous range of sorted points; it is staged through LDS in chunks with coalesced
+//     structure-of-arrays loads, and each lane scans only its own sub-range of the chunk (direct
+//     scan), or, in tiles whose lanes' sub-ranges differ widely, the passes of all sub-ranges are
+//     dealt out evenly over the lanes whichever query they belong to (flattened scan);
 //   * a candidate that beats the lane's current k-th best is appended to a small per-lane
-//     pending buffer in LDS (one write, no ordering work).  When any lane's buffer is nearly
-//     full, and at the end of every shell, all lanes absorb their pending keys into the sorted
-//     register list with a fixed merging network (no data-dependent addressing);
+//     pending buffer in LDS (one write, no ordering work).  When any lane's buffer is full, and
+//     at the end of every shell, all lanes absorb their pending keys into the sorted register
+//     list with a fixed merging network (no data-dependent addressing, no LDS round trips);
 //   * keys are 64-bit (distance bits << 32 | original index); slots beyond K-1 are pinned with
-//     zero keys so that the last register is always the last wanted key (list sizes 16/32/48/64;
-//     longer lists take a second pass that counts only keys above the first pass's last one);
-//   * a tile that straddles row splits walks once per row split with the other lanes switched
-//     off, so inside a walk the grid geometry is uniform;
+//     zero keys so that the last register is always the last wanted key (list sizes 16/32/48/64; longer
+//     lists take a second pass that counts only keys above the first pass's last one);
 //   * finished rows leave from the registers in 16-byte pieces when K equals the list size, else
 //     through LDS so that each output row is written as contiguous bytes;
+//   * the stage takes what the LDS budget of a workgroup leaves, and that budget is what lets as
+//     many workgroups share a CU as the registers allow;
 //   * lanes still uncertified when few are left are handed to the list kernel.
 #pragma once
-#include <type_traits>
 #include "fg_query.hpp"
 #include "fg_sortnet.hpp"
 
 namespace fg {
 
-// Waves per SIMD the register allocator aims at: the sorted list alone takes 2*KC registers.
+// Waves per SIMD the register allocator aims at: the sorted list alone takes 2*KC registers.  Measured choices:
+// KC = 32 at three (two are 18 % slower, four spill into the scan loop and are slower too); KC = 48 at three for
+// d <= 3 (12 % faster than two although a few registers spill outside the loops; with d >= 4 a staged candidate
+// takes two more vector registers per unrolled slot and three waves lose 8 %); 64 keys at two.
 template <int KC, int D> constexpr int tile_waves()
 {
     return KC <= 16 ? 4 : (KC == 32 ? 3 : (KC == 48 ? (D <= 3 ? 3 : 2) : 2));
 }
-constexpr int kPend = 16;             // pending keys per lane between two merges
-constexpr int kPendRows = kPend + 1;  // and one spare slot that takes the stores of candidates a lane does not keep
-constexpr int kRow = 16;              // queries per sub-tile: one DPP row
-constexpr int kRows = kQueryBlock / kRow;
-constexpr int kStepGroup = 4;         // candidates evaluated between two checks of the pending buffers
-constexpr int kSub = 2;               // candidates per lane in a chunk
-constexpr int kChunk = kSub * kRow;   // candidates of a row in a chunk
-constexpr int kMaxShellCols = 2048;   // columns a row may enumerate in one shell; beyond, its queries go to the list kernel
+constexpr int kPend = 16;   // pending keys per lane between two merges
+constexpr int kContinueLanes = 48;   // unfinished lanes a wave needs to go on past shell 1 (more than 2 binning dims)
+struct Ranges { int32_t a1, b1, a2, b2; };
 
 // row pitch of the output transposition in LDS: 65 words, so that the lanes writing one output row (consecutive
 // slots of one query) read 65 words apart and spread over the banks instead of all landing in one
 constexpr int kDumpStride = kQueryBlock + 1;
+constexpr int kUnroll = 4;  // candidates per lane per pass of the scan loop (independent LDS reads in flight)
 
-// ---- DPP helpers: all within one row of 16 lanes; every lane of the wave must be enabled -----------------
-template <int J> __device__ __forceinline__ int32_t row_bcast_i32(int32_t v)
-{
-    return __builtin_amdgcn_update_dpp(0, v, 0x150 + J, 0xf, 0xf, true);     // row_newbcast:J
-}
-template <int J> __device__ __forceinline__ float row_bcast_f32(float v)
-{
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x150 + J, 0xf, 0xf, true));
-}
-// reductions over the 16 lanes of a row, result in all of them: butterflies inside quads, across quads of a
-// half row (half mirror), across the halves (mirror)
-#define FG_ROW_REDUCE(NAME, T, OP)                                                                         \
-    __device__ __forceinline__ T NAME(T v)                                                                 \
-    {                                                                                                      \
-        v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xb1, 0xf, 0xf, false)));  \
-        v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4e, 0xf, 0xf, false)));  \
-        v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xf, 0xf, false))); \
-        v = OP(v, __builtin_bit_cast(T, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xf, 0xf, false))); \
-        return v;                                                                                          \
-    }
-__device__ __forceinline__ int32_t op_min_i32(int32_t a, int32_t b) { return a < b ? a : b; }
-__device__ __forceinline__ int32_t op_max_i32(int32_t a, int32_t b) { return a > b ? a : b; }
-__device__ __forceinline__ uint32_t op_max_u32(uint32_t a, uint32_t b) { return a > b ? a : b; }
-FG_ROW_REDUCE(row_min_i32, int32_t, op_min_i32)
-FG_ROW_REDUCE(row_max_i32, int32_t, op_max_i32)
-FG_ROW_REDUCE(row_max_u32, uint32_t, op_max_u32)
-FG_ROW_REDUCE(row_min_f32, float, fminf)
-FG_ROW_REDUCE(row_max_f32, float, fmaxf)
-#undef FG_ROW_REDUCE
-// inclusive prefix sum over the 16 lanes of a row
-__device__ __forceinline__ int32_t row_incl_scan_i32(int32_t v)
-{
-    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
-    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
-    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
-    return v;
-}
-
-template <int I, int N, class F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
-    }
-}
+// staged point = its D coordinates followed by its original index, padded to whole float4s
+template <int D> constexpr int stage_vecs() { return (D + 1 + 3) / 4; }
 
 // One whole output row from the lane that holds it: word 0 and the keys best[OFF ...], as 16-byte stores.
 // The row has KC - OFF + 1 words, a multiple of four, and starts on a 16-byte boundary.
@@ -131,98 +75,71 @@ __device__ __forceinline__ void store_row_from_registers(const uint64_t (&best)[
     }
 }
 
-// LDS of a workgroup (one wavefront): the pending buffers (8 KB) and the run tables of the four rows (1 KB);
-// at the end the same memory carries the output transposition.
-constexpr size_t kPendBytes = (size_t)kPendRows * kQueryBlock * 8;
-constexpr size_t kRunTableBytes = (size_t)kQueryBlock * 4 * 4;
-template <int KC> constexpr size_t tile_lds_bytes()
+constexpr int kTileFlatBit = 6;   // in a tile's class word: the ordering kernels found the tile uneven
+constexpr int kOrderFlagBit = 30;  // the same flag in the tile's entry of the order (tiles number below 2^25)
+// LDS of a workgroup (one wavefront): the pending buffers (8 KB), the stage, and for the flattened scan its tables.
+// How many wavefronts a CU holds is set by the registers (tile_waves) only if 4 * tile_waves workgroups fit its
+// 160 KB of LDS, so the stage is sized for that: 16 workgroups (lists of 16 keys) get 10 KB each, 12 get 12.5 KB
+// (measured: 12.6 KB still gives 12, 13.1 KB gives 11), 8 get 20 KB.  With a fixed 256-point stage d >= 4 ran at
+// 9 and d >= 8 at 7 wavefronts per CU instead of 12, and 16-key lists at 13 instead of 16: 1M uniform points,
+// K = 32: d = 4 1.17 -> 0.95 ms, d = 5 2.80 -> 2.31 ms, d = 8 51 -> 41 ms; d = 3, K = 16: 0.31 -> 0.27 ms.
+constexpr size_t kPendBytes = (size_t)kPend * kQueryBlock * 8;
+constexpr size_t kFlatTables = (size_t)kQueryBlock * 4 * 3 + 8 + (size_t)kQueryBlock * 8;   // counters, runs, starts, lower bounds
+template <int KC, int D> constexpr size_t tile_lds_budget()
 {
-    const size_t scan = kPendBytes + kRunTableBytes;
-    const size_t out = (size_t)kQueryBlock * 4 * 2 + (size_t)KC * kDumpStride * 4;
-    return scan > out ? scan : out;
+    return tile_waves<KC, D>() >= 4 ? 10240 : (tile_waves<KC, D>() == 3 ? 12800 : 20480);
+}
+constexpr int chunk_that_fits(size_t bytes, int nv)    // points: a multiple of 16 in [64, 256], kUnroll more are padding
+{
+    const int room = (int)(bytes / ((size_t)nv * 16)) - kUnroll;
+    const int chunk = room / 16 * 16;
+    return chunk > kStageChunk ? kStageChunk : (chunk < 64 ? 64 : chunk);
+}
+template <int KC, int D> constexpr int direct_chunk() { return chunk_that_fits(tile_lds_budget<KC, D>() - kPendBytes, stage_vecs<D>()); }
+// the flattened scan is compiled in where its tables leave room for a stage of at least 64 points
+template <int KC, int D> constexpr bool tile_has_flat()
+{
+    return tile_lds_budget<KC, D>() >= kPendBytes + kFlatTables + (size_t)stage_vecs<D>() * 16 * (64 + kUnroll);
+}
+template <int KC, int D> constexpr int flat_chunk()
+{
+    return tile_has_flat<KC, D>() ? chunk_that_fits(tile_lds_budget<KC, D>() - kPendBytes - kFlatTables, stage_vecs<D>()) : 64;
 }
 
-// Evaluates candidate J of every row against the row's 16 queries and appends what a lane keeps to its
-// pending buffer.  c[], ci: this lane's candidate (coordinates, original index); xq[]: this lane's query
-// (NaN in a lane that must keep nothing); INTRA: the candidates are the row's own queries, lane J skips itself.
-template <int J, int D, bool LOWER, bool INTRA>
-__device__ __forceinline__ void scan_step(const float (&c)[D], int32_t ci, const float (&xq)[D], uint32_t tau_hi,
-                                          uint64_t lower, uint32_t& pend_top, uint32_t spare, int rl)
+template <int D, int DB, int KC, bool COUNT, bool LOWER, bool FLAT>
+__device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile, uint64_t* lds64)
 {
-    // (candidate - query) squared equals (query - candidate) squared bit for bit; summed left to right
-    float diff = row_bcast_f32<J>(c[0]) - xq[0];
-    float d2 = diff * diff;
-#pragma unroll
-    for (int k = 1; k < D; ++k) {
-        diff = row_bcast_f32<J>(c[k]) - xq[k];
-        d2 = d2 + diff * diff;
-    }
-    const uint32_t idx = (uint32_t)row_bcast_i32<J>(ci);
-    const uint32_t bits = __float_as_uint(d2);
-    // kept if its distance does not exceed the k-th best's (a tie on the distance may lose on the index: the
-    // merge decides); NaN patterns (poisoned candidates, switched-off queries) lie above every bound
-    // No branch and no change of the execution mask: every lane stores every candidate at its slot pointer, and
-    // only a lane that keeps the candidate moves the pointer on, so what is not kept is overwritten by the next
-    // store.  (Narrowing the mask per step made every step a chain of vector compare -> scalar mask -> store ->
-    // scalar restore that three wavefronts per SIMD cannot hide.)  Index word and distance word are kPendRows
-    // planes apart.
-    static_assert(kPendRows == 17 && kQueryBlock * 4 == 0x100, "offsets below");
-    if constexpr (!INTRA && !LOWER) {
-        // A candidate that is not kept has a distance above the k-th best's, so it does no harm where it stays
-        // if nothing overwrites it: the merge reads all kPend slots and drops it like any key above the k-th best
-        // (slot kPend, beyond the last one the merge reads, takes the store of a lane whose buffer is full).
-        asm volatile("ds_write2st64_b32 %0, %1, %2 offset1:17" : : "v"(pend_top), "v"(idx), "v"(bits));
-        pend_top = bits <= tau_hi ? pend_top + 0x100u : pend_top;
-    } else {
-        // here a candidate can be turned down although it lies below the k-th best (the query itself, a key the
-        // first pass of a long list has already placed): it must not stay in a slot the merge reads
-        bool keep = bits <= tau_hi;
-        if (INTRA) keep = keep && rl != J;
-        if (LOWER) keep = keep && ((((uint64_t)bits << 32) | idx) > lower);
-        const uint32_t addr = keep ? pend_top : spare;
-        asm volatile("ds_write2st64_b32 %0, %1, %2 offset1:17" : : "v"(addr), "v"(idx), "v"(bits));
-        pend_top = keep ? pend_top + 0x100u : pend_top;
-    }
-}
-
-template <int D, int DB, int KC, bool COUNT, bool LOWER>
-__global__ void __launch_bounds__(kQueryBlock) __attribute__((amdgpu_waves_per_eu(tile_waves<KC, D>(), tile_waves<KC, D>())))
-k_query_tile(QueryArgs a)
-{
-    extern __shared__ uint64_t lds64[];
-    // an entry of the order: the tile, heaviest first
-    const int32_t tile = a.tile_order ? a.tile_order[blockIdx.x] : (int32_t)blockIdx.x;
+    constexpr int CHUNK = FLAT ? flat_chunk<KC, D>() : direct_chunk<KC, D>();
+    // LDS: [pending kPend x 64 keys][stage: CHUNK + kUnroll points of NV float4s][tables of the flattened scan];
+    //      re-used at the end as
+    //      [rows 64 words][KC x 64 words of the sorted lists, indices first, distances second]
     const int lane = threadIdx.x;
-    const int rl = lane & (kRow - 1);
-    const int row_lane0 = lane & ~(kRow - 1);
-    // pending keys: index words [kPendRows][64], then distance words [kPendRows][64]
+    // pending keys: index words [kPend][64], then distance words [kPend][64]
     uint32_t* const pend_lds = reinterpret_cast<uint32_t*>(lds64) + lane;
-    constexpr int kPendHalf = kPendRows * kQueryBlock;
+    constexpr int kPendHalf = kPend * kQueryBlock;
     // next free slot of this lane, kept as a plain LDS byte address so that an accepted candidate costs one
-    // two-word store and one add
+    // two-word store and one add (a pointer relative to pend_lds cost a second add per candidate)
     using lds_word = __attribute__((address_space(3))) uint32_t;
     const uint32_t pend_base = (uint32_t)(uintptr_t)(lds_word*)pend_lds;
     uint32_t pend_top = pend_base;
-    const uint32_t pend_full = pend_base + (kPend - kStepGroup) * kQueryBlock * 4;   // beyond this a group of steps may overflow
-    const uint32_t pend_spare = pend_base + kPend * kQueryBlock * 4;
-    // run tables of the four rows, one entry per column of the current batch of 16: offset of the column's
-    // candidates in the row's stream, first run (start, length), start of the second run
-    int32_t* const run_excl = reinterpret_cast<int32_t*>(lds64 + kPendRows * kQueryBlock) + row_lane0;
-    int32_t* const run_a1 = run_excl + kQueryBlock;
-    int32_t* const run_len1 = run_a1 + kQueryBlock;
-    int32_t* const run_a2 = run_len1 + kQueryBlock;
+    constexpr int NV = stage_vecs<D>();
+    float4* stage = reinterpret_cast<float4*>(lds64 + kPend * kQueryBlock);   // [CHUNK + kUnroll][NV]
+    // flattened scan only: after the stage, [64] pending counts, [64] run descriptors, [66] run starts in the
+    // flattened order, [64] lower bounds
+    uint32_t* const pend_cnt = reinterpret_cast<uint32_t*>(stage + (CHUNK + kUnroll) * NV);
+    int32_t* const fl_info = reinterpret_cast<int32_t*>(pend_cnt + kQueryBlock);
+    int32_t* const fl_start = fl_info + kQueryBlock;
+    uint64_t* const qlower = reinterpret_cast<uint64_t*>(fl_start + kQueryBlock + 2);
+    const uint64_t lt_mask = (1ull << lane) - 1;
 
     const int32_t cap = a.k_list;         // 0 <= cap <= KC
     const int32_t p = tile * kQueryBlock + lane;
     const bool valid = p < a.n;
-    const int32_t pp = valid ? p : a.n - 1;   // dead lanes shadow the last point, never scan or write
-    const int32_t my_row = a.perm[pp];
+    LaneGeom<D, DB> s;
+    s.init_geom(a, valid ? p : a.n - 1);  // dead lanes shadow the last point, never scan or write
+    const int32_t my_row = a.perm[valid ? p : a.n - 1];
     const bool asks = !(a.dir && !dir_is_query(a.dir[my_row]));   // direction flag: does this point query at all
-    const bool is_neighbour = !(a.dir && !dir_is_neighbour(a.dir[my_row]));
-    bool active = valid && cap > 0 && asks;   // still searching (any row split)
-    float x[D];
-#pragma unroll
-    for (int c = 0; c < D; ++c) x[c] = a.soa[(int64_t)c * a.soa_stride + pp];
+    bool active = valid && cap > 0 && asks;
     // second pass of a long list (more than 64 neighbours): the first pass has placed the 64 nearest; only keys
     // above the last of them count now (an empty slot there: the row split has no more points, nothing counts)
     uint64_t lower = 0;
@@ -236,345 +153,375 @@ k_query_tile(QueryArgs a)
     for (int i = 0; i < KC; ++i) best[i] = (i < KC - cap) ? 0ull : kEmptyKey;
 #pragma unroll
     for (int i = 0; i < kPend; ++i) pend_lds[kPendHalf + i * kQueryBlock] = (uint32_t)(kEmptyKey >> 32);   // all pending slots empty
-    uint32_t tau_hi = (uint32_t)(best[KC - 1] >> 32);
-    uint64_t tau = best[KC - 1];
+    if constexpr (FLAT) {
+        pend_cnt[lane] = 0;
+        fl_start[kQueryBlock] = 0x7fffffff;
+        if (LOWER) qlower[lane] = lower;
+    }
     int32_t cand = 0;
-    int32_t resume = 0;        // first shell the list kernel has to search for this lane, if it is handed over
-    bool handed = false;
+    int32_t useful = 0;   // candidates this lane evaluated
+    int32_t passes = 0;   // scan passes of the wave (kUnroll lane slots each)
 
     auto absorb = [&]() {
         uint64_t pend[kPend];
-        asm volatile("" : : : "memory");     // the stores of the steps above are issued before these reads
         // unused slots hold the empty key's distance word (refilled below), whatever their index word: such keys
         // lie at or above the empty key and sort behind every real one
-        // (the sign bit of the distance word is cleared: a slot may hold a candidate that was not kept, whose
-        // distance may be a NaN of either sign, and the networks order keys as non-negative doubles)
 #pragma unroll
         for (int i = 0; i < kPend; ++i)
-            pend[i] = ((uint64_t)(pend_lds[kPendHalf + i * kQueryBlock] & 0x7fffffffu) << 32) | pend_lds[i * kQueryBlock];
+            pend[i] = ((uint64_t)pend_lds[kPendHalf + i * kQueryBlock] << 32) | pend_lds[i * kQueryBlock];
 #pragma unroll
         for (int i = 0; i < kPend; ++i) pend_lds[kPendHalf + i * kQueryBlock] = (uint32_t)(kEmptyKey >> 32);
         net_sort<kPend>(pend);
         net_absorb<KC, kPend>(best, pend);
         pend_top = pend_base;
-        tau = best[KC - 1];
-        tau_hi = (uint32_t)(tau >> 32);
-        asm volatile("" : : : "memory");     // and the refill above before the stores of the steps that follow
+        s.tau = best[KC - 1];
+        if constexpr (FLAT) {
+            pend_cnt[lane] = 0;
+            __syncthreads();
+        }
     };
 
-    // the row splits this tile touches; each gets a walk of its own
-    const int32_t p_last = tile * kQueryBlock + kQueryBlock - 1 < a.n - 1 ? tile * kQueryBlock + kQueryBlock - 1 : a.n - 1;
-    const int32_t seg_first = segment_of(a.row_splits, a.n_segments, tile * kQueryBlock);
-    const int32_t seg_last = segment_of(a.row_splits, a.n_segments, p_last);
-    const float kNaN = __uint_as_float(0x7fc00000u);
-
-    for (int32_t seg = seg_first; seg <= seg_last; ++seg) {
-        const int32_t s0 = a.row_splits[seg], s1 = a.row_splits[seg + 1];
-        const bool in_seg = valid && p >= s0 && p < s1;
-        bool act = active && in_seg;                      // searching in this walk
-        if (!__any(act)) continue;
-        // grid of the row split (uniform over the wave), this lane's bin in it
-        float glo[DB], gw[DB], gslack[DB];
-        int32_t neff[DB], cc[DB];
-        {
-            const float* g = a.geom + (int64_t)seg * DB * kGeomStride;
+    int32_t R = 0;
+    const uint32_t pend_full = pend_base + (kPend - kUnroll) * kQueryBlock * 4;   // beyond this a pass may overflow
+    for (;; ++R) {   // ends at the latest at R = n_bins - 1, when every lane's cube covers its grid
+        const int32_t side = 2 * R + 1;
+        int32_t ncols = 1;
 #pragma unroll
-            for (int c = 0; c < DB; ++c) {
-                const float inv_w = g[c * kGeomStride + 1];
-                glo[c] = g[c * kGeomStride + 0];
-                gw[c] = g[c * kGeomStride + 2];
-                gslack[c] = g[c * kGeomStride + 3];
-                cc[c] = cell_of(x[c], glo[c], inv_w, a.n_bins);
-                neff[c] = inv_w > 0.0f ? a.n_bins : 1;
-            }
-        }
-        const int32_t seg_cell0 = seg * a.cells_per_segment;
-        // true when no point of a box at squared lower-bound distance b2 can enter a list whose k-th best is t
-        auto cannot_improve = [&](uint64_t t, float b2) -> bool {
-            return t < kEmptyKey && b2 > 1e-30f && __uint_as_float((uint32_t)(t >> 32)) < b2 * kBoundShrink;
-        };
-        // after shell r: may this lane stop (the cube of radius r round its bin is searched)
-        auto certified = [&](int32_t r) -> bool {
-            bool covered = true;
-            float mingap = 3.0e38f;
+        for (int c = 0; c < DB - 1; ++c) ncols *= side;
+        // this lane's candidate ranges for column t of shell R: up to two runs of sorted positions
+        auto prepare = [&](int32_t t) -> Ranges {
+            // column offsets, wave-uniform; digit v of t maps to 0, +1, -1, +2, -2, ... (centre first)
+            int32_t o[DB - 1];
+            bool surf = false;
+            {
+                int32_t rem = t;
 #pragma unroll
-            for (int c = 0; c < DB; ++c) {
-                const int32_t jl = cc[c] - r, jh = cc[c] + r;
-                if (jl > 0) {
-                    covered = false;
-                    const float g = x[c] - (glo[c] + (float)jl * gw[c]) - gslack[c];
-                    mingap = fminf(mingap, g > 0.0f ? g : 0.0f);
-                }
-                if (jh < neff[c] - 1) {
-                    covered = false;
-                    const float g = (glo[c] + (float)(jh + 1) * gw[c]) - x[c] - gslack[c];
-                    mingap = fminf(mingap, g > 0.0f ? g : 0.0f);
+                for (int c = DB - 2; c >= 0; --c) {
+                    const int32_t v = rem % side;
+                    rem /= side;
+                    o[c] = (v & 1) ? ((v + 1) >> 1) : -(v >> 1);
+                    surf = surf || o[c] == R || o[c] == -R;
                 }
             }
-            return covered || cannot_improve(tau, mingap * mingap);
-        };
-        // box of the row's queries of this walk in the binned coordinates: bounds every lane's distance to a bin from below
-        float qmin[DB], qmax[DB];
-#pragma unroll
-        for (int c = 0; c < DB; ++c) {
-            qmin[c] = row_min_f32(in_seg ? x[c] : 3.0e38f);
-            qmax[c] = row_max_f32(in_seg ? x[c] : -3.0e38f);
-        }
-        float xq[D];   // what the scan sees as this lane's query
-#pragma unroll
-        for (int c = 0; c < D; ++c) xq[c] = act ? x[c] : kNaN;
-
-        // ---- the row's own 16 points: every lane against the 15 others (they are left out of the streams below)
-        {
-            float cself[D];
-            const bool offer = in_seg && is_neighbour;
-#pragma unroll
-            for (int c = 0; c < D; ++c) cself[c] = offer ? x[c] : kNaN;
-            static_for<0, kRow>([&](auto J) {
-                scan_step<decltype(J)::value, D, LOWER, true>(cself, my_row, xq, tau_hi, lower, pend_top, pend_spare, rl);
-            });
-            if (COUNT && act) cand += __popcll(__ballot(in_seg) & (0xffffull << row_lane0)) - 1;
-            if (__any(pend_top > pend_full)) absorb();     // up to 15 kept per lane: make room for the first group of steps
-        }
-        const int32_t own0 = tile * kQueryBlock + row_lane0;                  // the row's own sorted positions
-        const int32_t own1 = own0 + kRow;
-
-        int32_t rdone = -1;    // last shell this lane took part in, in this walk
-        bool give_up = false;  // this lane's row cannot enumerate its columns: to the list kernel
-        int32_t R = 0;
-        for (;; ++R) {   // ends at the latest at R = n_bins - 1, when every lane's cube covers its grid
-            // who asks for columns in this shell: at shell 0 every point of the walk (so that the row's own points
-            // are certainly inside the region, whatever their flags), afterwards the searching lanes
-            const bool want = R == 0 ? in_seg : act;
-            const int32_t ra = want ? R : -1;                             // radius this lane reaches now
-            const int32_t rp = R == 0 ? -1 : (act ? R - 1 : rdone);       // radius this lane's columns were searched to
-            // columns to enumerate: the box of the asking lanes' columns, widened by R, centre first
-            int32_t c0[DB - 1], side[DB - 1];
-            int32_t ncols = row_max_i32(act ? 1 : 0);    // a row without searching lanes has nothing to enumerate
-            bool too_many = false;
+            bool ok = active;
+            float partial = 0.0f;
+            int32_t flat = 0;
 #pragma unroll
             for (int c = 0; c < DB - 1; ++c) {
-                const int32_t lo = row_min_i32(want ? cc[c] : 0x7fffffff);
-                const int32_t hi = row_max_i32(want ? cc[c] : -1);
-                const int32_t e = hi >= lo ? hi - lo : 0;
-                c0[c] = (hi >= lo ? lo : 0) + (e >> 1);
-                side[c] = 2 * (R + ((e + 1) >> 1)) + 1;
-                if (hi < lo) ncols = 0;
-                too_many = too_many || side[c] > kMaxShellCols || ncols * side[c] > kMaxShellCols;
-                ncols = too_many ? 0 : ncols * side[c];
+                const int32_t j = s.cc[c] + o[c];
+                ok = ok && j >= 0 && j < s.neff[c];
+                const float g = s.gap(c, j, o[c]);
+                partial += g * g;
+                flat = flat * a.n_bins + j;
             }
-            if (too_many) { give_up = give_up || act; ncols = 0; }
-            const bool wants_now = want && !give_up;
-            const int32_t ra_now = wants_now ? ra : -1;
-            const uint64_t tau_row = ((uint64_t)row_max_u32(act ? (uint32_t)(tau >> 32) : 0u) << 32) | 0xffffffffu;   // no searching lane's k-th best is above this
-            const int32_t max_cols = wave_max_i32(ncols);
-
-            for (int32_t t0 = 0; t0 < max_cols; t0 += kRow) {
-                // ---- this lane's column of its row: which bins of it are new in this shell
-                const int32_t t = t0 + rl;
-                bool ok = t < ncols;
-                int32_t X[DB - 1];
-                float partial = 0.0f;
-                int32_t flat = 0;
-                {
-                    int32_t rem = ok ? t : 0;
-#pragma unroll
-                    for (int c = DB - 2; c >= 0; --c) {
-                        // digit v of the column number maps to offset 0, +1, -1, +2, -2, ... from the centre
-                        const int32_t q = (int32_t)(((float)rem + 0.5f) * (1.0f / (float)side[c]));   // exact: rem < 2^11 * side
-                        const int32_t v = rem - q * side[c];
-                        rem = q;
-                        X[c] = c0[c] + ((v & 1) ? ((v + 1) >> 1) : -(v >> 1));
+            ok = ok && !s.cannot_improve(partial);
+            int32_t a1 = 0, b1 = 0, a2 = 0, b2 = 0;
+            if (ok) {
+                const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
+                const int32_t row = s.seg_cell0 + flat * a.n_bins;
+                if (surf) {
+                    int32_t za = cz - R < 0 ? 0 : cz - R;
+                    int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
+                    // drop end bins of the run whose box is already too far
+                    while (za < cz) {
+                        const float g = s.gap(DB - 1, za, za - cz);
+                        if (!s.cannot_improve(partial + g * g)) break;
+                        ++za;
                     }
-#pragma unroll
-                    for (int c = 0; c < DB - 1; ++c) {
-                        ok = ok && X[c] >= 0 && X[c] < neff[c];
-                        // distance from the box of the row's queries to the bin, from below
-                        const float below = qmin[c] - (glo[c] + (float)(X[c] + 1) * gw[c]) - gslack[c];
-                        const float above = (glo[c] + (float)X[c] * gw[c]) - qmax[c] - gslack[c];
-                        const float gp = fmaxf(fmaxf(below, above), 0.0f);
-                        partial += gp * gp;
-                        flat = snake_push(flat, ok ? X[c] : 0, a.n_bins);
+                    while (zb > cz) {
+                        const float g = s.gap(DB - 1, zb, zb - cz);
+                        if (!s.cannot_improve(partial + g * g)) break;
+                        --zb;
+                    }
+                    a1 = a.bounds[row + za];
+                    b1 = a.bounds[row + zb + 1];
+                    if (R == 0) { a2 = p + 1; b2 = b1; b1 = p; }   // the query's own bin, the query itself left out
+                } else {
+                    if (cz - R >= 0) {
+                        const float g = s.gap(DB - 1, cz - R, -R);
+                        if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[row + cz - R]; b1 = a.bounds[row + cz - R + 1]; }
+                    }
+                    if (cz + R <= nz - 1) {
+                        const float g = s.gap(DB - 1, cz + R, R);
+                        if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[row + cz + R]; b2 = a.bounds[row + cz + R + 1]; }
                     }
                 }
-                // union over the row's queries that reach this column: what was searched before (plo..phi), what
-                // this shell asks for (alo..ahi)
-                int32_t plo = 0x7fffffff, phi = -0x7fffffff, alo = 0x7fffffff, ahi = -0x7fffffff;
-                static_for<0, kRow>([&](auto J) {
-                    constexpr int j = decltype(J)::value;
-                    int32_t rmin = 0;
+            }
+            return Ranges{a1, b1, a2, b2};
+        };
+        Ranges cur = prepare(0);
+        for (int32_t t = 0; t < ncols; ++t) {
+            // the next column's bin boundaries are requested before this column is scanned, so
+            // their latency hides behind the scan (its pruning sees a k-th best one column old)
+            Ranges nxt = Ranges{0, 0, 0, 0};
+            if (t + 1 < ncols) nxt = prepare(t + 1);
+            const int32_t a1 = cur.a1, b1 = cur.b1, a2 = cur.a2, b2 = cur.b2;
+            cur = nxt;
+            int32_t lo = 0x7fffffff, hi = 0;
+            if (b1 > a1) { lo = a1; hi = b1; }
+            if (b2 > a2) { lo = a2 < lo ? a2 : lo; hi = b2 > hi ? b2 : hi; }
+            const int32_t PA = wave_min_i32(lo), PB = wave_max_i32(hi);
+            for (int32_t base = PA; base < PB; base += CHUNK) {
+                const int32_t cnt_pts = PB - base < CHUNK ? PB - base : CHUNK;
+                __syncthreads();
+                for (int32_t i = lane; i < cnt_pts; i += kQueryBlock) {
+                    float w[NV * 4];
 #pragma unroll
-                    for (int c = 0; c < DB - 1; ++c) {
-                        const int32_t dlt = row_bcast_i32<j>(cc[c]) - X[c];
-                        rmin = op_max_i32(rmin, dlt < 0 ? -dlt : dlt);
+                    for (int c = 0; c < NV * 4; ++c) w[c] = 0.0f;
+#pragma unroll
+                    for (int c = 0; c < D; ++c) w[c] = a.soa[(int64_t)c * a.soa_stride + base + i];
+                    const int32_t src = a.perm[base + i];
+                    w[D] = __int_as_float(src);
+                    if (a.dir && !dir_is_neighbour(a.dir[src])) {          // never a neighbour: poison its coordinates
+#pragma unroll
+                        for (int c = 0; c < D; ++c) w[c] = __uint_as_float(0x7fc00000u);
                     }
-                    const int32_t zj = row_bcast_i32<j>(cc[DB - 1]);
-                    const int32_t rpj = row_bcast_i32<j>(rp);
-                    const int32_t raj = row_bcast_i32<j>(ra_now);
-                    if (rmin <= rpj) { plo = op_min_i32(plo, zj - rpj); phi = op_max_i32(phi, zj + rpj); }
-                    if (rmin <= raj) { alo = op_min_i32(alo, zj - raj); ahi = op_max_i32(ahi, zj + raj); }
-                });
-                ok = ok && ahi >= alo && !cannot_improve(tau_row, partial);
-                int32_t a1 = 0, b1 = 0, a2 = 0, b2 = 0;
-                if (ok) {
-                    const int32_t nz = neff[DB - 1];
-                    // last-dimension bins new in this shell: below and above what was searched before
-                    int32_t z1a, z1b, z2a, z2b;
-                    if (phi < plo) { z1a = alo; z1b = ahi; z2a = 1; z2b = 0; }
-                    else { z1a = alo; z1b = plo - 1; z2a = phi + 1; z2b = ahi; }
-                    z1a = z1a < 0 ? 0 : z1a; z1b = z1b > nz - 1 ? nz - 1 : z1b;
-                    z2a = z2a < 0 ? 0 : z2a; z2b = z2b > nz - 1 ? nz - 1 : z2b;
-                    // drop end bins whose box is too far for every searching lane of the row
-                    auto far_below = [&](int32_t z) {
-                        const float g = fmaxf(qmin[DB - 1] - (glo[DB - 1] + (float)(z + 1) * gw[DB - 1]) - gslack[DB - 1], 0.0f);
-                        return cannot_improve(tau_row, partial + g * g);
-                    };
-                    auto far_above = [&](int32_t z) {
-                        const float g = fmaxf((glo[DB - 1] + (float)z * gw[DB - 1]) - qmax[DB - 1] - gslack[DB - 1], 0.0f);
-                        return cannot_improve(tau_row, partial + g * g);
-                    };
-                    while (z1a <= z1b && far_below(z1a)) ++z1a;
-                    if (phi < plo) { while (z1b >= z1a && far_above(z1b)) --z1b; }
-                    while (z2b >= z2a && far_above(z2b)) --z2b;
-                    int32_t f0, f1;
-                    if (z1b >= z1a) { snake_run(flat, z1a, z1b, a.n_bins, &f0, &f1); a1 = a.bounds[seg_cell0 + f0]; b1 = a.bounds[seg_cell0 + f1 + 1]; }
-                    if (z2b >= z2a) { snake_run(flat, z2a, z2b, a.n_bins, &f0, &f1); a2 = a.bounds[seg_cell0 + f0]; b2 = a.bounds[seg_cell0 + f1 + 1]; }
-                    if (R == 0) {
-                        // the row's own points are not streamed: cut them out of the (single) run
-                        if (a1 < own1 && b1 > own0) {
-                            a2 = own1 > a1 ? own1 : a1; b2 = b1;
-                            b1 = own0 < b1 ? own0 : b1;
-                            if (b2 < a2) b2 = a2;
-                            if (b1 < a1) b1 = a1;
-                        }
-                    }
+#pragma unroll
+                    for (int v = 0; v < NV; ++v) stage[i * NV + v] = make_float4(w[4 * v], w[4 * v + 1], w[4 * v + 2], w[4 * v + 3]);
                 }
-                const int32_t len1 = b1 - a1, len = len1 + (b2 - a2);
-                const int32_t incl = row_incl_scan_i32(len);
-                const int32_t T = row_bcast_i32<kRow - 1>(incl);          // candidates of the row in this batch of columns
                 __syncthreads();
-                run_excl[rl] = incl - len; run_a1[rl] = a1; run_len1[rl] = len1; run_a2[rl] = a2;
-                __syncthreads();
-                const int32_t n_chunks = (wave_max_i32(T) + kChunk - 1) / kChunk;
-
-                // A chunk is kSub candidates per lane (kSub x 16 per row): candidate (ch * kSub + u) * 16 + L of the
-                // row's stream goes to register set u of lane L.  The loads of chunk ch + 1 are issued before chunk
-                // ch is evaluated; they take well over a microsecond under load, which the kSub x 16 steps of a chunk
-                // (with the other wavefronts of the SIMD) cover, and 16 steps do not.  All loads of a fetch are
-                // independent and unconditional (slots beyond the end of the stream read a valid dummy position and
-                // are poisoned afterwards): a load that waits for another one's result would expose a full memory
-                // latency per chunk.
-                struct Stage { float c[kSub][D]; int32_t ci[kSub]; };
-                // this lane's place in the table: the run its last candidate came from and where that run ends in the
-                // stream; candidates are taken in ascending order, so the next one is found by stepping forward
-                int32_t cj = -1, c_end = 0, c_excl = 0;
-                auto fetch = [&](int32_t ch, Stage& st) {
+                if constexpr (!FLAT) {
+                // this lane's two sub-ranges clipped to the chunk, walked one after the other
+                const int32_t top = base + cnt_pts;
+                int32_t q = a1 > base ? a1 : base, e = b1 < top ? b1 : top;
+                int32_t q2 = a2 > base ? a2 : base, e2 = b2 < top ? b2 : top;
+                useful += (e > q ? e - q : 0) + (e2 > q2 ? e2 - q2 : 0);
+                const bool second_runs = __any(e2 > q2);      // only the centre column (and shell 0) has two runs per lane
+                for (;;) {
+                    if (second_runs && q >= e && q2 < e2) { q = q2; e = e2; q2 = e2; }
+                    const int32_t rem = e - q;
+                    if (!__any(rem > 0)) break;
+                    float w[kUnroll][NV * 4];
+                    const uint32_t tau_hi = (uint32_t)(s.tau >> 32);
+                    const int32_t i0 = rem > 0 ? q - base : 0;       // reads past the lane's range stay inside the padded chunk
 #pragma unroll
-                    for (int u = 0; u < kSub; ++u) {
-                        const int32_t f = (ch * kSub + u) * kRow + rl;
-                        const bool in = f < T;
-                        while (in && f >= c_end) {       // runs of length zero are stepped over; the last run ends at T > f
-                            ++cj;
-                            c_excl = c_end;
-                            c_end = cj + 1 < kRow ? run_excl[cj + 1] : T;
+                    for (int u = 0; u < kUnroll; ++u) {
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) {
+                            const float4 f = stage[(i0 + u) * NV + v];
+                            w[u][4 * v] = f.x; w[u][4 * v + 1] = f.y; w[u][4 * v + 2] = f.z; w[u][4 * v + 3] = f.w;
                         }
-                        const int32_t jj = cj < 0 ? 0 : cj;
-                        const int32_t local = f - c_excl, l1 = run_len1[jj];
-                        int32_t q = local < l1 ? run_a1[jj] + local : run_a2[jj] + (local - l1);
-                        q = in ? q : pp;
-                        // index of the candidate, or -1 if a direction flag says it is nobody's neighbour (a.perm_cand
-                        // is a.perm where there are no flags)
-                        st.ci[u] = a.perm_cand[q];
-#pragma unroll
-                        for (int c = 0; c < D; ++c) st.c[u][c] = a.soa[(int64_t)c * a.soa_stride + q];
                     }
-                };
-                Stage nxt, cur;
-                if (n_chunks > 0) fetch(0, nxt);
-                for (int32_t ch = 0; ch < n_chunks; ++ch) {
 #pragma unroll
-                    for (int u = 0; u < kSub; ++u) {
-                        // a slot beyond the end of the stream, or a point that is nobody's neighbour: its coordinates
-                        // become NaN (the loads were issued a chunk ago, unconditionally)
-                        const int32_t f = (ch * kSub + u) * kRow + rl;
-                        const bool real = f < T && nxt.ci[u] >= 0;
+                    for (int u = 0; u < kUnroll; ++u) {
+                        float diff = s.x[0] - w[u][0];
+                        float d2 = diff * diff;
 #pragma unroll
-                        for (int c = 0; c < D; ++c) cur.c[u][c] = real ? nxt.c[u][c] : kNaN;
-                        cur.ci[u] = nxt.ci[u];
+                        for (int c = 1; c < D; ++c) {
+                            diff = s.x[c] - w[u][c];
+                            d2 = d2 + diff * diff;
+                        }
+                        const bool live = u < rem;
+                        if (COUNT) cand += live;
+                        // kept if its distance does not exceed the k-th best's (a tie on the distance may lose
+                        // on the index: the merge decides); NaN (poisoned) patterns lie above every bound
+                        const uint32_t bits = __float_as_uint(d2);
+                        if (live && bits <= tau_hi && (!LOWER || (((uint64_t)bits << 32) | __float_as_uint(w[u][D])) > lower)) {
+                            // index word and distance word kPend planes apart, then the slot pointer moves on:
+                            // written out because the compiler spends a third instruction on a register copy
+                            static_assert(kPendHalf * 4 == 16 * 256 && kQueryBlock * 4 == 0x100, "offsets below");
+                            asm volatile("ds_write2st64_b32 %0, %1, %2 offset1:16\n\tv_add_u32 %0, 0x100, %0"
+                                         : "+v"(pend_top) : "v"(__float_as_uint(w[u][D])), "v"(bits) : "memory");
+                        }
                     }
-                    if (COUNT && act) { const int32_t left = T - ch * kChunk; cand += left > kChunk ? kChunk : (left > 0 ? left : 0); }
-                    fetch(ch + 1, nxt);          // beyond the last chunk: a harmless fetch of padding
-#pragma unroll 1
-                    for (int g = 0; g < kChunk / kStepGroup; ++g) {
-                        static_for<0, kChunk / kStepGroup>([&](auto G) {
-                            constexpr int gg = decltype(G)::value;
-                            constexpr int u = gg / (kRow / kStepGroup), j0 = (gg % (kRow / kStepGroup)) * kStepGroup;
-                            if (g == gg) {
-                                static_for<j0, j0 + kStepGroup>([&](auto J) {
-                                    scan_step<decltype(J)::value, D, LOWER, false>(cur.c[u], cur.ci[u], xq, tau_hi, lower, pend_top, pend_spare, rl);
-                                });
+                    q += kUnroll;
+                    ++passes;
+                    if (__any(pend_top > pend_full)) absorb();
+                }
+                } else {
+                // Flattened scan: the work of this chunk is dealt out evenly over the lanes, whichever query it belongs
+                // to.  Every query's clipped run is cut into passes of kUnroll candidates; the passes of all queries
+                // are put in one order (prefix sum over the lanes) and lane L takes passes [L*C, (L+1)*C) of it.  What
+                // a lane keeps goes to the pending buffer of the query the pass belongs to (slots from a counter in
+                // LDS), and that query's lane merges it as before.
+                const int32_t top = base + cnt_pts;
+                const int32_t q = a1 > base ? a1 : base, e = b1 < top ? b1 : top;
+                const int32_t q2 = a2 > base ? a2 : base, e2 = b2 < top ? b2 : top;
+                const int32_t len1 = e > q ? e - q : 0, len2 = e2 > q2 ? e2 - q2 : 0;
+                useful += len1 + len2;
+                if (COUNT) cand += len1 + len2;
+                const bool second_runs = __any(len2 > 0);      // only the centre column (and shell 0) has two runs per lane
+                for (int run = 0; run < 2; ++run) {
+                    if (run == 1 && !second_runs) break;
+                    const int32_t len = run ? len2 : len1;
+                    const uint64_t m = __ballot(len > 0);
+                    if (m == 0) continue;
+                    const int32_t nq = __popcll(m);
+                    const int32_t ng = (len + kUnroll - 1) / kUnroll;          // passes this run takes
+                    const int32_t incl = wave_incl_scan_dpp_i32(ng);
+                    const int32_t TG = __builtin_amdgcn_readlane(incl, kQueryBlock - 1);
+                    __syncthreads();
+                    if (len > 0) {
+                        const int32_t rank = __popcll(m & lt_mask);
+                        fl_start[rank] = incl - ng;
+                        static_assert(CHUNK <= 512, "run start and length are packed in 10 bits each");
+                        fl_info[rank] = ((run ? q2 : q) - base) | (len << 10) | (lane << 20);
+                    }
+                    if (lane >= nq) fl_start[lane] = 0x7fffffff;
+                    __syncthreads();
+                    const int32_t C = (TG + kQueryBlock - 1) / kQueryBlock;
+                    int32_t f = lane * C;
+                    const int32_t f_end = f + C < TG ? f + C : TG;
+                    int32_t j = 0;
+#pragma unroll
+                    for (int step = 32; step > 0; step >>= 1)
+                        if (fl_start[j + step] <= f) j += step;
+                    int32_t run_end = f, pos = 0, left = 0, owner = lane;
+                    float xq[D];
+                    uint32_t tau_hi = 0;
+                    // The lane's place in run j: where the run's candidates sit in the stage, how many are left, and
+                    // the query it belongs to, whose coordinates and k-th best are read from that query's lane
+                    // (cross-lane reads return nothing from a lane that is switched off: every lane executes this,
+                    // lanes without work with a harmless run number, and `take` says who keeps the result).
+                    auto load_run = [&](bool take) {
+                        const int32_t info = fl_info[j];
+                        const int32_t first = fl_start[j], nxt_start = fl_start[j + 1];
+                        const int32_t from = info >> 20;
+                        float xo[D];
+#pragma unroll
+                        for (int c = 0; c < D; ++c) xo[c] = __shfl(s.x[c], from, 64);
+                        const uint32_t to = (uint32_t)__shfl((int)(uint32_t)(s.tau >> 32), from, 64);
+                        if (take) {
+                            owner = from;
+                            pos = (info & 0x3ff) + (f - first) * kUnroll;
+                            left = ((info >> 10) & 0x3ff) - (f - first) * kUnroll;
+                            run_end = nxt_start < f_end ? nxt_start : f_end;
+#pragma unroll
+                            for (int c = 0; c < D; ++c) xq[c] = xo[c];
+                            tau_hi = to;
+                        }
+                    };
+#pragma unroll
+                    for (int c = 0; c < D; ++c) xq[c] = 0.0f;
+                    load_run(f < f_end);
+                    for (;;) {
+                        const bool busy = f < run_end;
+                        if (!__any(busy)) break;
+                        const int32_t rem = busy ? left : 0;
+                        float w[kUnroll][NV * 4];
+                        const int32_t i0 = busy ? pos : 0;          // reads past the run stay inside the padded chunk
+#pragma unroll
+                        for (int u = 0; u < kUnroll; ++u) {
+#pragma unroll
+                            for (int v = 0; v < NV; ++v) {
+                                const float4 g = stage[(i0 + u) * NV + v];
+                                w[u][4 * v] = g.x; w[u][4 * v + 1] = g.y; w[u][4 * v + 2] = g.z; w[u][4 * v + 3] = g.w;
                             }
-                        });
-                        if (__any(pend_top > pend_full)) absorb();
+                        }
+                        uint32_t bits[kUnroll];
+                        bool acc[kUnroll];
+                        int32_t na = 0;
+                        uint64_t low = 0;
+                        if (LOWER) low = qlower[owner];
+#pragma unroll
+                        for (int u = 0; u < kUnroll; ++u) {
+                            float diff = xq[0] - w[u][0];
+                            float d2 = diff * diff;
+#pragma unroll
+                            for (int c = 1; c < D; ++c) {
+                                diff = xq[c] - w[u][c];
+                                d2 = d2 + diff * diff;
+                            }
+                            bits[u] = __float_as_uint(d2);
+                            // kept if its distance does not exceed the k-th best's (a tie on the distance may lose on
+                            // the index: the merge decides); NaN (poisoned) patterns lie above every bound
+                            acc[u] = u < rem && bits[u] <= tau_hi &&
+                                     (!LOWER || (((uint64_t)bits[u] << 32) | __float_as_uint(w[u][D])) > low);
+                            na += acc[u] ? 1 : 0;
+                        }
+                        bool fail = false, hot = false;
+                        if (na > 0) {
+                            const int32_t s0 = (int32_t)atomicAdd(&pend_cnt[owner], (uint32_t)na);
+                            fail = s0 + na > kPend;                 // no room: nothing is stored, the pass is repeated
+                            hot = s0 + na > kPend - kUnroll;        // the next pass might not fit
+                            if (!fail) {
+                                static_assert(kPendHalf * 4 == 16 * 256 && kQueryBlock * 4 == 0x100, "offsets below");
+                                uint32_t wptr = (pend_base - (uint32_t)lane * 4u) + (uint32_t)owner * 4u + (uint32_t)s0 * (kQueryBlock * 4u);
+#pragma unroll
+                                for (int u = 0; u < kUnroll; ++u) {
+                                    if (acc[u]) {
+                                        asm volatile("ds_write2st64_b32 %0, %1, %2 offset1:16\n\tv_add_u32 %0, 0x100, %0"
+                                                     : "+v"(wptr) : "v"(__float_as_uint(w[u][D])), "v"(bits[u]) : "memory");
+                                    }
+                                }
+                            }
+                        }
+                        if (busy && !fail) { ++f; pos += kUnroll; left -= kUnroll; }
+                        ++passes;
+                        const bool merge = __any(hot);
+                        if (merge) { __syncthreads(); absorb(); }
+                        const bool next_run = f >= run_end && f < f_end;
+                        if (__any(next_run)) {
+                            if (next_run) ++j;
+                            load_run(next_run);
+                        }
+                        if (merge) tau_hi = (uint32_t)__shfl((int)(uint32_t)(s.tau >> 32), owner, 64);   // tightened by the merge
                     }
                 }
+                }
             }
-            if (__any(pend_top != pend_base)) absorb();
-            // shell R is searched for every lane that asked and was not given up
-            if (want && !give_up) rdone = R;
-            if (act && give_up) { act = false; handed = true; resume = R; }
-            if (act && certified(R)) act = false;
-            if (!act) {
-#pragma unroll
-                for (int c = 0; c < D; ++c) xq[c] = kNaN;
-            }
-            const int32_t n_act = __popcll(__ballot(act));
-            if (n_act == 0) break;
-            // Go on to the next shell in this wave only while enough of its lanes still search: a shell costs the
-            // whole wave the union of what its unfinished lanes need, and the list kernel takes a query from
-            // where it stands for a few microseconds of one wavefront.
-            if (R >= 1 && n_act <= a.defer_lanes) break;
         }
-        // unfinished lanes of this walk go to the list kernel
-        if (act) { handed = true; resume = R + 1; }
-        active = active && !in_seg;
+        if constexpr (FLAT) {
+            __syncthreads();
+            if (__any(pend_cnt[lane] != 0)) absorb();
+        } else {
+            if (__any(pend_top != pend_base)) absorb();
+        }
+        if (active && s.certified(R)) active = false;
+        const int32_t n_active = __popcll(__ballot(active));
+        if (n_active == 0) break;
+        if (R >= 1) {
+            // Go on to the next shell in this wave only if that is efficient.  Shell R + 1 costs the whole wave
+            // (2R+3)^(DB-1) columns however few of its lanes still search, and the list kernel takes a query
+            // from where it stands for a few microseconds of one wavefront: beyond two binning dimensions the
+            // wave goes on only while most of its lanes (48 of 64) are unfinished (grids made for two shells, as
+            // for d >= 6, or a fine grid on uniform data); measured on 1M uniform points, d = 5: 4.5 -> 3.5 ms,
+            // d = 6: 14.2 -> 13.3 ms against the previous rule of 7 lanes.  With two binning dimensions the next
+            // shell is a handful of long columns and 7 lanes are enough.  In either case the lanes must have
+            // been evenly loaded so far (candidates evaluated vs lane slots spent): an uneven tile (sparse lanes
+            // next to a dense cluster) keeps 64 lanes waiting for a few.
+            if (n_active <= a.defer_lanes) break;
+            if (DB > 2 && n_active < kContinueLanes) break;
+            const int32_t spent = passes * kUnroll;
+            if (wave_sum_i32(useful) * 5 < spent * kQueryBlock * 2) break;     // below 40 % lane use
+        }
     }
 
-    // handed-over lanes go to the work list (wave-aggregated append); their lists so far leave with the
+    // unfinished lanes go to the work list (wave-aggregated append); their lists so far leave with the
     // finished rows, and the first shell still to search travels in slot 0 of the distance row
-    const uint64_t mask = __ballot(handed);
+    const uint64_t mask = __ballot(active);
     if (mask) {
         int32_t base = 0;
         const int leader = __ffsll((unsigned long long)mask) - 1;
         if (lane == leader) base = atomicAdd(a.work_count, __popcll(mask));
         base = __shfl(base, leader, 64);
-        if (handed) a.work_list[base + __popcll(mask & ((1ull << lane) - 1))] = p;
+        if (active) a.work_list[base + __popcll(mask & ((1ull << lane) - 1))] = p;
     }
-    const uint32_t resume_word = handed ? (uint32_t)resume : 0u;
-
+    const uint32_t resume_word = (uint32_t)(R + 1);
     // Rows of exactly KC words (K = 16, 32, 48, 64) leave straight from the registers: every lane writes its own
     // row in 16-byte pieces (the pieces of a 128-byte line arrive within a few instructions of each other and are
-    // joined in the L2 cache).  Rows that do not start on a 64-byte boundary (K = 40: 160 bytes) keep the
-    // transposition.
+    // joined in the L2 cache).  A sixteenth of the instructions of the transposition below: query stage -8 % at
+    // K = 16, -4 % at K = 32, +-0 at K = 64.  Rows that do not start on a 64-byte boundary (K = 40: 160 bytes)
+    // were 3 % slower this way and keep the transposition.
     const bool direct_rows = a.slot0 == 0 && a.k == KC && cap == KC - 1 &&
                              (((uintptr_t)a.out_idx | (uintptr_t)a.out_d2) & 15) == 0;
-    if (COUNT && valid) a.out_cand[my_row] = LOWER ? a.out_cand[my_row] + cand : cand;
     if (direct_rows) {
+        if (COUNT && valid) a.out_cand[my_row] = LOWER ? a.out_cand[my_row] + cand : cand;
         if (valid) {
             int32_t* oi = a.out_idx + (int64_t)my_row * a.k;
             float* od = a.out_d2 + (int64_t)my_row * a.k;
-            store_row_from_registers<KC, 1>(best, oi, od, asks ? my_row : -1, resume_word);
+            const int32_t idx0 = asks ? my_row : -1;
+            const uint32_t d2_0 = ((mask >> lane) & 1) ? resume_word : 0u;     // handed over: where to resume
+            store_row_from_registers<KC, 1>(best, oi, od, idx0, d2_0);
         }
-        return;
-    }
+    } else {
     // otherwise: registers -> LDS -> contiguous row writes
     __syncthreads();
     // two passes (indices, then distances) so the transposition needs KC x 64 words, not keys
     int32_t* rows_lds = reinterpret_cast<int32_t*>(lds64);
-    uint32_t* resume_lds = reinterpret_cast<uint32_t*>(lds64) + kQueryBlock;
-    uint32_t* dump = reinterpret_cast<uint32_t*>(lds64) + 2 * kQueryBlock;     // [KC][65] after the row and resume words
+    uint32_t* dump = reinterpret_cast<uint32_t*>(lds64) + kQueryBlock;     // [KC][64] after the 64 row words
     rows_lds[lane] = valid ? (asks ? my_row : -2 - my_row) : -1;   // -1: nothing to write; <= -2: all-padding row
-    resume_lds[lane] = resume_word;
+    if (COUNT && valid) a.out_cand[my_row] = LOWER ? a.out_cand[my_row] + cand : cand;
     const int32_t k = a.k;
     const int32_t kk = cap + 1;                                         // words written per row: slot 0 and this pass's slots
     const int32_t per_iter = kk >= kQueryBlock ? 1 : kQueryBlock / kk;  // rows written per pass
@@ -598,7 +545,8 @@ k_query_tile(QueryArgs a)
             if (enc == -1) continue;
             const int32_t row = enc >= 0 ? enc : -2 - enc;
             for (int32_t j = j0; j < kk; j += kQueryBlock) {
-                uint32_t word = pass == 0 ? (enc >= 0 ? (uint32_t)row : 0xffffffffu) : resume_lds[ql];   // slot 0: the row itself at distance 0, or where to resume
+                uint32_t word = pass == 0 ? (enc >= 0 ? (uint32_t)row : 0xffffffffu) : 0u;   // slot 0: the row itself at distance 0
+                if (pass == 1 && ((mask >> ql) & 1)) word = resume_word;                     // handed over: where to resume
                 if (j > 0) word = dump[(KC - cap + j - 1) * kDumpStride + ql];
                 const int32_t slot = j > 0 ? a.slot0 + j : 0;
                 if (pass == 0) a.out_idx[(int64_t)row * k + slot] = (int32_t)word;
@@ -606,6 +554,40 @@ k_query_tile(QueryArgs a)
             }
         }
     }
+    }
+}
+
+// The kernel: one workgroup of one wavefront per tile.  Tiles the ordering kernels marked as uneven take the
+// flattened scan, all others, and every tile of an unordered launch, the direct one.  One kernel with a branch,
+// not two kernels: a tile alone takes ~0.1 ms from its first shell to its last row whatever runs beside it, so a
+// second kernel for the uneven tiles adds its whole tail.  a.algo == 2 sends every tile to the flattened scan
+// (tests).  The counting instantiation scans directly.
+template <int D, int DB, int KC, bool COUNT, bool LOWER>
+__global__ void __launch_bounds__(kQueryBlock) __attribute__((amdgpu_waves_per_eu(tile_waves<KC, D>(), tile_waves<KC, D>())))
+k_query_tile_sorted(QueryArgs a)
+{
+    extern __shared__ uint64_t lds64[];
+    // an entry of the order: the tile, heaviest first, and above it the flag of an uneven tile
+    const int32_t entry = a.tile_order ? a.tile_order[blockIdx.x] : (int32_t)blockIdx.x;
+    const int32_t tile = entry & ((1 << kOrderFlagBit) - 1);
+    if constexpr (!COUNT && tile_has_flat<KC, D>()) {
+        const bool uneven = a.algo == 2 || ((entry >> kOrderFlagBit) & 1);
+        if (uneven) {
+            tile_body<D, DB, KC, COUNT, LOWER, true>(a, tile, lds64);
+            return;
+        }
+    }
+    tile_body<D, DB, KC, COUNT, LOWER, false>(a, tile, lds64);
+}
+
+template <int KC, int D>
+constexpr size_t tile_sorted_lds_bytes()
+{
+    const size_t flat = kPendBytes + (size_t)stage_vecs<D>() * 16 * (flat_chunk<KC, D>() + kUnroll) + kFlatTables;
+    const size_t direct = kPendBytes + (size_t)stage_vecs<D>() * 16 * (direct_chunk<KC, D>() + kUnroll);
+    const size_t out = (size_t)kQueryBlock * 4 + (size_t)KC * kDumpStride * 4;
+    const size_t scan = (tile_has_flat<KC, D>() && flat > direct) ? flat : direct;
+    return scan > out ? scan : out;
 }
 
 }  // namespace fg

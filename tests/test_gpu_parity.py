@@ -218,10 +218,11 @@ def test_tile_and_list_kernels_both_run_and_agree_with_the_plain_walk():
 
 @pytest.mark.parametrize("d,k", [(2, 20), (3, 9), (3, 16), (3, 32), (3, 40), (3, 64), (4, 33), (5, 25), (6, 48), (8, 64), (10, 20),
                                  (3, 100), (3, 128)])
-def test_clustered_points_every_list_size(d, k):
-    """Every list size and both passes of a long list on clustered points with duplicates, a short and an empty
-    split (tiles that straddle row splits walk once per split), with and without direction flags, through the
-    two calls a training step makes (bin, then query on that binning)."""
+def test_flattened_scan_on_every_tile(d, k):
+    """algo = 2: the tile kernel's flattened scan (the work of a chunk dealt out evenly over the lanes, kept
+    candidates appended to their query's pending buffer from any lane) on every tile, for every list size and
+    both passes of a long list.  Clustered points with duplicates, a short and an empty split, direction
+    flags."""
     rng = np.random.Generator(np.random.PCG64(500 + 10 * d + k))
     sizes = [2300, 5, 0, 1700]
     n = sum(sizes)
@@ -233,16 +234,16 @@ def test_clustered_points_every_list_size(d, k):
     oi, od = oracle.knn(x, rs, k)
     for nb in (0, 7):
         bn = B.fg_bin_points(xt, rt, k, nb, min(d, 3) if nb else 0)
-        gi, gd = B.fg_query_binned(bn, rt, k)
+        gi, gd = B.fg_query_binned(bn, rt, k, algo=2)
         torch.cuda.synchronize()
-        assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "clustered d=%d k=%d nb=%d" % (d, k, nb))
+        assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "flattened d=%d k=%d nb=%d" % (d, k, nb))
     direction = rng.integers(0, 4, size=n).astype(np.int32)
     oi, od = oracle.knn(x, rs, k, direction=direction)
     bn = B.fg_bin_points(xt, rt, k)
     dt = torch.from_numpy(direction).to(DEV)
-    gi, gd = B.fg_query_binned(bn, rt, k, direction=dt)
+    gi, gd = B.fg_query_binned(bn, rt, k, direction=dt, algo=2)
     torch.cuda.synchronize()
-    assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "clustered with flags d=%d k=%d" % (d, k))
+    assert_exact(gi.cpu().numpy(), gd.cpu().numpy(), oi, od, "flattened with flags d=%d k=%d" % (d, k))
 
 
 def test_ordered_launch_takes_every_tile_once():
@@ -347,14 +348,9 @@ def test_binning_invariants(d, nb, db):
         if size > 1:
             assert np.array_equal(geom[s, :, 0], x[rs[s]:rs[s + 1], :bn.d_bin].min(axis=0))
     # bins are monotone in every binned coordinate (what the search's lower bounds rely on)
-    # (bin numbers are serpentine: the digit of a dimension runs backwards when the number formed by the digits
-    # before it is odd, so that consecutive bins are neighbours in space)
     local = bin_idx - seg * T
-    prefix = np.zeros(n, dtype=np.int64)
     for c in range(bn.d_bin):
-        digit = (local // (bn.n_bins ** (bn.d_bin - 1 - c))) % bn.n_bins
-        cell_c = np.where(prefix % 2 == 1, bn.n_bins - 1 - digit, digit)
-        prefix = prefix * bn.n_bins + digit
+        cell_c = (local // (bn.n_bins ** (bn.d_bin - 1 - c))) % bn.n_bins
         for s, size in enumerate(sizes):
             if size > 1:
                 sl = slice(rs[s], rs[s + 1])
