@@ -131,6 +131,20 @@ fg_status fg_binned_select_knn(const float* coords, const int32_t* row_splits, i
                                int32_t d_bin, int32_t* out_idx, float* out_d2,
                                void* workspace, size_t workspace_bytes, void* stream);
 
+/* fg_binned_select_knn for callers that cannot allocate device memory or hand over a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, result and error behaviour
+ * as fg_binned_select_knn, without workspace: the scratch lives in a device array inside the library
+ * (FG_STATIC_SCRATCH_BYTES per GPU, held until the process ends).  The call allocates nothing and calls no
+ * allocating routine.  A problem whose workspace would be larger returns FG_ERR_WORKSPACE (nothing enqueued):
+ * roughly n * (4 d + 40) bytes plus 4 bytes per bin must fit, e.g. 600,000 points of d = 3.  Every call on a GPU
+ * uses that GPU's one array: calls that overlap in time on one GPU (different streams, different threads) race and
+ * must be serialised by the caller; calls in sequence on one stream are fine.  The array's address is looked up on
+ * the first call on each device (with that device current), which should therefore happen outside graph capture. */
+#define FG_STATIC_SCRATCH_BYTES (32u << 20)
+fg_status fg_binned_select_knn_static(const float* coords, const int32_t* row_splits, int64_t n,
+                                      int32_t d, int32_t n_segments, int32_t k, int32_t n_bins,
+                                      int32_t d_bin, int32_t* out_idx, float* out_d2, void* stream);
+
 /* Direction-flag variant (Algorithm 2, inputs useDir and dir[]): dir [n] int32, one flag per point:
  *   0  the point can be a neighbour but issues no query
  *   1  the point queries but is nobody's neighbour

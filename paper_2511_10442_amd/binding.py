@@ -23,7 +23,7 @@ FG_ERR_WORKSPACE = 4
 FG_ERR_LAUNCH = 5
 
 EXPORTS = ["fg_status_string", "fg_auto_n_bins", "fg_workspace_size", "fg_bin_points",
-           "fg_binned_select_knn", "fg_binned_select_knn_dir", "fg_binned_select_knn_counted", "fg_query_binned",
+           "fg_binned_select_knn", "fg_binned_select_knn_static", "fg_binned_select_knn_dir", "fg_binned_select_knn_counted", "fg_query_binned",
            "fg_knn_backward", "fg_knn_backward_binned", "fg_oc_helper", "fg_oc_helper_workspace_size"]
 
 
@@ -68,6 +68,8 @@ def lib() -> ctypes.CDLL:
                                     ctypes.POINTER(_Binning), vp]
         L.fg_binned_select_knn.restype = ctypes.c_int
         L.fg_binned_select_knn.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
+        L.fg_binned_select_knn_static.restype = ctypes.c_int
+        L.fg_binned_select_knn_static.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp]
         L.fg_binned_select_knn_dir.restype = ctypes.c_int
         L.fg_binned_select_knn_dir.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp, sz, vp]
         L.fg_binned_select_knn_counted.restype = ctypes.c_int
@@ -247,6 +249,25 @@ def fg_binned_select_knn(coords: torch.Tensor, row_splits: torch.Tensor, k: int,
     _check(lib().fg_binned_select_knn(_ptr(coords), _ptr(row_splits), n, d, s, k, n_bins, d_bin,
                                       _ptr(out_idx), _ptr(out_d2), _ptr(workspace),
                                       workspace.numel(), _stream()), "fg_binned_select_knn")
+    return out_idx, out_d2
+
+
+FG_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def fg_binned_select_knn_static(coords: torch.Tensor, row_splits: torch.Tensor, k: int, out_idx: torch.Tensor,
+                                out_d2: torch.Tensor, n_bins: int = 0, d_bin: int = 0):
+    """The entry point that allocates nothing: the caller passes inputs and outputs, the scratch is the library's
+    own device array.  (The binding allocates nothing either: both outputs are required.)"""
+    coords = _dev(coords, torch.float32, "coords")
+    row_splits = _dev(row_splits, torch.int32, "row_splits")
+    n, d = coords.shape
+    s = row_splits.numel() - 1
+    _out(out_idx, (n, k), torch.int32, coords.device, "out_idx")
+    _out(out_d2, (n, k), torch.float32, coords.device, "out_d2")
+    _check(lib().fg_binned_select_knn_static(_ptr(coords), _ptr(row_splits), n, d, s, k, n_bins, d_bin,
+                                             _ptr(out_idx), _ptr(out_d2), _stream()),
+           "fg_binned_select_knn_static")
     return out_idx, out_d2
 
 

@@ -1,6 +1,11 @@
 // C-ABI entry points: argument validation, workspace layout, stage launches.
 #include <math.h>
+#include <mutex>
 #include "fg_internal.hpp"
+
+// Workspace of fg_binned_select_knn_static: device memory that belongs to the library, one copy per GPU, held
+// until the process ends.  In host code this name is only a handle for hipGetSymbolAddress, never an address.
+static __device__ __align__(256) unsigned char scratch[FG_STATIC_SCRATCH_BYTES];
 
 namespace fg {
 
@@ -319,6 +324,41 @@ fg_status fg_binned_select_knn(const float* coords, const int32_t* row_splits, i
 {
     return knn_impl(coords, row_splits, nullptr, n, d, n_segments, k, n_bins, d_bin, out_idx, out_d2, nullptr, workspace,
                     workspace_bytes, stream);
+}
+
+// Address of `scratch` on the current device, looked up once per device.
+static fg_status static_scratch_address(void** out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* address[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return FG_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!address[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return FG_ERR_LAUNCH;
+        address[dev] = ptr;
+    }
+    *out = address[dev];
+    return FG_OK;
+}
+
+fg_status fg_binned_select_knn_static(const float* coords, const int32_t* row_splits, int64_t n,
+                                      int32_t d, int32_t n_segments, int32_t k, int32_t n_bins,
+                                      int32_t d_bin, int32_t* out_idx, float* out_d2, void* stream)
+{
+    fg_status st = check_problem(n, d, n_segments, k);
+    if (st != FG_OK) return st;
+    if (n == 0) return FG_OK;
+    st = resolve_bins(n, d, n_segments, k, &n_bins, &d_bin);
+    if (st != FG_OK) return st;
+    if (make_layout(n, d, n_segments, n_bins, d_bin).total > (size_t)FG_STATIC_SCRATCH_BYTES) return FG_ERR_WORKSPACE;
+    void* ws = nullptr;
+    st = static_scratch_address(&ws);
+    if (st != FG_OK) return st;
+    return knn_impl(coords, row_splits, nullptr, n, d, n_segments, k, n_bins, d_bin, out_idx, out_d2, nullptr, ws,
+                    (size_t)FG_STATIC_SCRATCH_BYTES, stream);
 }
 
 fg_status fg_binned_select_knn_dir(const float* coords, const int32_t* row_splits, const int32_t* dir,
