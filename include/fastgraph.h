@@ -19,7 +19,8 @@
  *   - Every call returns an fg_status; on any status other than FG_OK nothing was enqueued.
  *   - Preconditions that cannot be checked without a device round trip are documented, not
  *     checked: row_splits[0] = 0, row_splits[S] = n, non-decreasing; all coordinates finite.
- *   - n must be below 2^31 (indices are int32).  2 <= d <= 10.  1 <= k <= 128.
+ *   - n <= FG_MAX_N (indices are int32, and the launch arithmetic keeps a margin below 2^31).
+ *     n_segments <= FG_MAX_SEGMENTS.  2 <= d <= 10.  1 <= k <= 128.
  */
 #ifndef FASTGRAPH_H
 #define FASTGRAPH_H
@@ -34,13 +35,16 @@ extern "C" {
 typedef enum {
     FG_OK = 0,
     FG_ERR_NULL = 1,        /* a required pointer is NULL */
-    FG_ERR_BAD_SHAPE = 2,   /* n < 0, n >= 2^31, n_segments < 1, k < 1, n_bins/d_bin out of range, too many bins */
+    FG_ERR_BAD_SHAPE = 2,   /* n < 0, n > FG_MAX_N, n_segments < 1 or > FG_MAX_SEGMENTS, k < 1, n_bins/d_bin out of
+                               range, too many bins */
     FG_ERR_UNSUPPORTED = 3, /* d outside 2..10, k > 128, d_bin outside 2..5 */
     FG_ERR_WORKSPACE = 4,   /* workspace too small or not 256-byte aligned */
     FG_ERR_LAUNCH = 5       /* the HIP runtime reported an error at launch */
 } fg_status;
 
 /* Largest values accepted. */
+#define FG_MAX_N 2147418112       /* 2^31 - 2^16 points */
+#define FG_MAX_SEGMENTS (1 << 22)
 #define FG_MAX_D 10
 #define FG_MIN_D 2
 #define FG_MAX_K 128

@@ -108,7 +108,9 @@ Layout make_layout(int64_t n, int32_t d, int32_t n_segments, int32_t n_bins, int
 
 fg_status check_problem(int64_t n, int32_t d, int32_t n_segments, int32_t k)
 {
-    if (n < 0 || n >= ((int64_t)1 << 31) || n_segments < 1 || k < 1) return FG_ERR_BAD_SHAPE;
+    // n: launch grids and chunk counts are 32-bit sums of n and a block size; n_segments: offsets into the
+    // bounding-box keys and geometry records are 32-bit products of a few hundred and n_segments
+    if (n < 0 || n > FG_MAX_N || n_segments < 1 || n_segments > FG_MAX_SEGMENTS || k < 1) return FG_ERR_BAD_SHAPE;
     if (d < FG_MIN_D || d > FG_MAX_D || k > FG_MAX_K) return FG_ERR_UNSUPPORTED;
     return FG_OK;
 }

@@ -72,10 +72,11 @@ def check_properties(w, gi, gd):
 
 
 def check_digests(cfg, gi, gd, seg=None):
+    """Every row of the run against the oracle's complete result, through per-block digests written on the CPU by
+    tests/golden/make_config_digests.py.  The digest file must exist."""
     name = "config%d_digests.txt" % cfg if seg is None else "config%d_seg%d_digests.txt" % (cfg, seg)
     path = os.path.join(GOLDEN, name)
-    if not os.path.exists(path):
-        return False
+    assert os.path.exists(path), "missing oracle digests %s" % name
     want = [l.strip() for l in open(path) if l.strip() and not l.startswith("#")]
     w = workload(cfg)
     b0, e0 = (0, w.n) if seg is None else (int(w.row_splits[seg]), int(w.row_splits[seg + 1]))
@@ -88,7 +89,6 @@ def check_digests(cfg, gi, gd, seg=None):
     bad = [i for i, (g, o) in enumerate(zip(got, want)) if g != o]
     assert len(got) == len(want) and not bad, "config %d: %d of %d blocks differ from the oracle digests, first block %d" % (
         cfg, len(bad), len(want), bad[0] if bad else -1)
-    return True
 
 
 def sample_rows(n, count, seed):
@@ -160,6 +160,7 @@ def test_config2_full_forward_and_backward():
     check_properties(w, gi, gd)
     ref, asum = oracle.knn_backward(w.grad_d2, oi, w.coords)
     grad_close(backward_gpu(w.grad_d2, oi, w.coords, w.row_splits), ref, asum)
+    grad_close(backward_binned_gpu(w.grad_d2, oi, w.coords, w.row_splits, w.k), ref, asum)
     nb, db = B.fg_auto_n_bins(w.n, w.n_segments, w.k, w.d, mode=0)   # paper: 14 bins over 4 dims
     gi2, gd2 = forward(w, nb, db)
     assert np.array_equal(gi2, oi) and np.array_equal(gd2.view(np.uint32), od.view(np.uint32))
@@ -181,6 +182,27 @@ def test_config3_forward():
     gi3, gd3 = B.fg_query_binned(B.fg_bin_points(xt, rst, w.k, 0, 0, ws), rst, w.k)
     torch.cuda.synchronize()
     assert np.array_equal(gi3.cpu().numpy(), gi) and np.array_equal(gd3.cpu().numpy().view(np.uint32), gd.view(np.uint32))
+
+
+def real_graph_backward(cfg):
+    """The flow bench.py times, at full size: forward on the GPU (the index matrix is checked against the oracle's
+    digests first, so it IS the oracle's graph), then both backward entry points on that graph against the
+    double-precision oracle backward of the same matrix."""
+    w = workload(cfg)
+    gi, gd = forward(w)
+    if cfg == 5:
+        for seg in range(w.n_segments):
+            check_digests(5, gi, gd, seg=seg)
+    else:
+        check_digests(cfg, gi, gd)
+    ref, asum = oracle.knn_backward(w.grad_d2, gi, w.coords)
+    assert np.abs(ref).max() > 0
+    grad_close(backward_binned_gpu(w.grad_d2, gi, w.coords, w.row_splits, w.k), ref, asum)
+    grad_close(backward_gpu(w.grad_d2, gi, w.coords, w.row_splits), ref, asum)
+
+
+def test_config3_backward_on_the_real_graph():
+    real_graph_backward(3)
 
 
 def test_config3_backward():
@@ -223,12 +245,17 @@ def test_config5_forward():
     rows = sample_rows(w.n, 3000, seed=505)
     oi, od = oracle.knn_rows(w.coords, w.row_splits, w.k, rows)
     assert_rows_exact(gi, gd, oi, od, rows, "config 5")
-    check_digests(5, gi, gd, seg=0)
+    for seg in range(w.n_segments):
+        check_digests(5, gi, gd, seg=seg)
     # the densest spot: points closest to the origin of the first split
     r2 = np.sum(w.coords[: w.row_splits[1]].astype(np.float64) ** 2, axis=1)
     rows = np.sort(np.argsort(r2)[:300]).astype(np.int64)
     oi, od = oracle.knn_rows(w.coords, w.row_splits, w.k, rows)
     assert_rows_exact(gi, gd, oi, od, rows, "config 5 centre")
+
+
+def test_config5_backward_on_the_real_graph():
+    real_graph_backward(5)
 
 
 def test_config5_backward():
@@ -241,6 +268,26 @@ def test_config5_backward():
     ref, asum = oracle.knn_backward(w.grad_d2, idx, w.coords)
     grad_close(backward_gpu(w.grad_d2, idx, w.coords, w.row_splits), ref, asum)
     _cache.clear()
+
+
+@pytest.mark.parametrize("d", [2, 5, 8])
+def test_uniform_sweep_points_at_one_million(d):
+    """Three points of the uniform sweep (the paper's own benchmark shape, Section 4: 1M uniform random vectors,
+    K = 40) at full size in the launch configuration bench.py --sweep uniform times: sampled rows against the
+    oracle, every row against the size-independent properties."""
+    _cache.clear()
+    x, rs = W.uniform(1_000_000, d, seed=4000 + d)
+    k = 40
+    idx, d2 = B.fg_binned_select_knn(torch.from_numpy(x).to(DEV), torch.from_numpy(rs).to(DEV), k)
+    torch.cuda.synchronize()
+    gi, gd = idx.cpu().numpy(), d2.cpu().numpy()
+    rows = sample_rows(x.shape[0], 400, seed=600 + d)
+    oi, od = oracle.knn_rows(x, rs, k, rows)
+    assert_rows_exact(gi, gd, oi, od, rows, "uniform 1M d=%d" % d)
+
+    class _W:
+        coords, row_splits = x, rs
+    check_properties(_W, gi, gd)
 
 
 def test_output_larger_than_two_to_the_31_elements():

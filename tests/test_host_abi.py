@@ -95,6 +95,16 @@ def test_argument_validation_without_gpu():
     assert L.fg_knn_backward(8, 8, 8, 8, 10, 3, 1, 4, 8, 256, 16, None) == B.FG_ERR_WORKSPACE
     assert L.fg_knn_backward(None, None, None, None, 0, 3, 1, 4, None, None, 0, None) == B.FG_OK
     assert L.fg_query_binned(None, 8, 10, 3, 1, 4, 8, 8, None, None, None) == B.FG_ERR_NULL
+    # the top of the advertised range: accepted up to FG_MAX_N = 2^31 - 2^16 points, refused beyond (the launch
+    # arithmetic adds block sizes to n in 32 bits); likewise the number of row splits
+    big = ctypes.c_size_t(0)
+    assert L.fg_workspace_size(2147418112, 3, 1, 16, 0, 0, ctypes.byref(big)) == B.FG_OK and big.value > 2147418112 * 4 * 8
+    for n_bad in (2147418113, 2 ** 31 - 1024, 2 ** 31 - 1, 2 ** 31, 2 ** 40):
+        assert L.fg_workspace_size(n_bad, 3, 1, 16, 0, 0, ctypes.byref(big)) == B.FG_ERR_BAD_SHAPE
+        assert L.fg_binned_select_knn(8, 8, n_bad, 3, 1, 16, 0, 0, 8, 8, 256, 1 << 40, None) == B.FG_ERR_BAD_SHAPE
+        assert L.fg_knn_backward(8, 8, 8, None, n_bad, 3, 1, 16, 8, None, 0, None) == B.FG_ERR_BAD_SHAPE
+    assert L.fg_workspace_size(10 ** 6, 3, (1 << 22) + 1, 16, 0, 0, ctypes.byref(big)) == B.FG_ERR_BAD_SHAPE
+    assert L.fg_workspace_size(10 ** 7, 3, 1 << 22, 16, 2, 2, ctypes.byref(big)) == B.FG_OK
     assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 4, 10, 1, 1, None, 8, None, 0, None) == B.FG_ERR_NULL
     assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 4, 10, 1, 1, 8, None, None, 0, None) == B.FG_ERR_NULL
     assert L.fg_oc_helper(8, 8, 8, 8, 10, 2, 1, 0, 10, 0, 1, 8, None, None, 0, None) == B.FG_ERR_BAD_SHAPE
