@@ -39,7 +39,9 @@ typedef enum {
                                range, too many bins */
     FG_ERR_UNSUPPORTED = 3, /* d outside 2..10, k > 128, d_bin outside 2..5 */
     FG_ERR_WORKSPACE = 4,   /* workspace too small or not 256-byte aligned */
-    FG_ERR_LAUNCH = 5       /* the HIP runtime reported an error at launch */
+    FG_ERR_LAUNCH = 5,      /* the HIP runtime reported an error at launch */
+    FG_STATUS_INT_RANGE = 0x7fffffff   /* not a status: makes every non-negative int a valid value of the type on
+                                          both sides of the boundary (C callers pass plain ints) */
 } fg_status;
 
 /* Largest values accepted. */
