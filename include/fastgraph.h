@@ -81,16 +81,17 @@ typedef struct {
     const int32_t* bin_idx;    /* [n]  flat bin of each point, ORIGINAL order; segment s owns bins [s*T, (s+1)*T); inside
                                   a segment the bins are numbered row-major over the grid, last binning dimension
                                   fastest (the flattening of Algorithm 1) */
-    const int32_t* perm;       /* [n]  sorted position -> original row index */
     const int32_t* bin_bounds; /* [n_segments*T + 1] exclusive prefix of bin populations: bin b holds
                                   sorted positions [bin_bounds[b], bin_bounds[b+1]) */
-    const float* sorted_soa;   /* [d][soa_stride] coordinates in bin order, structure of arrays */
+    const float* sorted_points;/* [n][record_floats] the points in bin order, one record each: the d coordinates, then
+                                  the original row index (an int32 stored in the float's 4 bytes), then zeros.  The
+                                  index fields, read in order, are the permutation sorted position -> original row */
     const float* seg_geom;     /* [n_segments][d_bin][4]: lower box edge, bins per unit length (0 if the
                                   segment has zero extent in that dimension), bin width, rounding slack */
-    int64_t soa_stride;        /* elements between consecutive coordinate rows of sorted_soa */
     int64_t cells_per_segment; /* T = n_bins^d_bin */
     int32_t n_bins;            /* bins per binning dimension actually used */
     int32_t d_bin;             /* binning dimensions actually used (the first d_bin coordinates) */
+    int32_t record_floats;     /* floats per record of sorted_points: d + 1 rounded up to a multiple of 4 */
     void* scratch;             /* opaque: scratch of the query stage inside the workspace.  Its first int32 holds, after
                                   fg_query_binned, the number of queries the tile kernel handed to the list kernel (a
                                   diagnostic; nothing else in it is meant to be read) */
@@ -104,7 +105,7 @@ typedef struct {
                                   flattened scan on every tile instead of the uneven ones only (for tests) */
     int32_t defer_lanes;       /* after shell 1 a wavefront of the tile kernel goes on to the next shell only while
                                   more than this many of its 64 queries are unfinished, the rest go to the list
-                                  kernel; 0..64, negative: the default */
+                                  kernel; 0..64, negative: the default (64 for d <= 5, 6 beyond) */
 } fg_query_options;
 
 /* Spatial partition + counting sort (Section 3, second paragraph: bins per row split, points ordered by bin,

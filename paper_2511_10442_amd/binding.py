@@ -34,11 +34,10 @@ class FgError(RuntimeError):
 
 
 class _Binning(ctypes.Structure):
-    _fields_ = [("bin_idx", ctypes.c_void_p), ("perm", ctypes.c_void_p),
-                ("bin_bounds", ctypes.c_void_p), ("sorted_soa", ctypes.c_void_p),
-                ("seg_geom", ctypes.c_void_p), ("soa_stride", ctypes.c_int64),
+    _fields_ = [("bin_idx", ctypes.c_void_p), ("bin_bounds", ctypes.c_void_p),
+                ("sorted_points", ctypes.c_void_p), ("seg_geom", ctypes.c_void_p),
                 ("cells_per_segment", ctypes.c_int64), ("n_bins", ctypes.c_int32),
-                ("d_bin", ctypes.c_int32), ("scratch", ctypes.c_void_p)]
+                ("d_bin", ctypes.c_int32), ("record_floats", ctypes.c_int32), ("scratch", ctypes.c_void_p)]
 
 
 class _QueryOptions(ctypes.Structure):
@@ -149,7 +148,7 @@ class Binning:
     n_bins: int
     d_bin: int
     cells_per_segment: int
-    soa_stride: int
+    record_floats: int
 
     def _view(self, ptr: int, count: int, dtype) -> torch.Tensor:
         off = ptr - self.workspace.data_ptr()
@@ -161,16 +160,23 @@ class Binning:
         return self._view(self.raw.bin_idx, self.n, torch.int32)
 
     @property
+    def sorted_records(self):
+        """[n, record_floats] float32: coordinates, original row index (int32 bits), zero padding."""
+        return self._view(self.raw.sorted_points, self.n * self.record_floats, torch.float32).view(self.n, self.record_floats)
+
+    @property
     def perm(self):
-        return self._view(self.raw.perm, self.n, torch.int32)
+        """Sorted position -> original row: the index field of the records."""
+        return self.sorted_records.view(torch.int32)[:, self.d].contiguous()
+
+    @property
+    def sorted_coords(self):
+        """[n, d] coordinates in bin order."""
+        return self.sorted_records[:, :self.d]
 
     @property
     def bin_bounds(self):
         return self._view(self.raw.bin_bounds, self.n_segments * self.cells_per_segment + 1, torch.int32)
-
-    @property
-    def sorted_soa(self):
-        return self._view(self.raw.sorted_soa, self.d * self.soa_stride, torch.float32).view(self.d, self.soa_stride)
 
     @property
     def work_count(self):
@@ -197,7 +203,7 @@ def fg_bin_points(coords: torch.Tensor, row_splits: torch.Tensor, k_hint: int, n
                                _ptr(workspace), workspace.numel(), ctypes.byref(raw), _stream()),
            "fg_bin_points")
     return Binning(raw, workspace, n, d, s, int(raw.n_bins), int(raw.d_bin),
-                   int(raw.cells_per_segment), int(raw.soa_stride))
+                   int(raw.cells_per_segment), int(raw.record_floats))
 
 
 def _out(t, shape, dtype, device, name: str) -> torch.Tensor:

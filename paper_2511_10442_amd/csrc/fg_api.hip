@@ -56,7 +56,14 @@ constexpr size_t kAlign = 256;
 // (1M uniform points, K = 40: d = 8 67 -> 54 ms, d = 10 243 -> 179 ms against 1.6; configuration 4 34 -> 28 ms).
 constexpr double kTunedMarginByDim[11] = {0, 0, 0.9, 0.9, 0.9, 0.9, 1.6, 1.85, 1.85, 1.85, 1.85};
 constexpr int32_t kTunedMaxBins = 1024;
-constexpr int32_t kDefaultDeferLanes = 6;
+// Hand-over threshold of the tile kernel (fg_query_options::defer_lanes).  Up to five dimensions every query that
+// is not certified after shell 1 goes to the list kernel (64: a wavefront never starts shell 2): the automatic grids
+// there are made for one shell, what is left after it are the sparse neighbourhoods, and one query per wavefront
+// takes those from where they stand faster than a tile does with most of its lanes idle (1M-point clustered
+// workload -6 %, the 100k-point Gaussian mixture -23 %, uniform data -1..-5 %).  From six dimensions on the grids
+// are made for two shells and a tile goes on while more than 6 lanes search (always handing over: +19 % at d = 6,
+// x2 at d = 8).
+constexpr int32_t default_defer_lanes(int32_t d) { return d <= 5 ? 64 : 6; }
 constexpr int kScanChunkHost = 256 * 16;   // must match the scan kernels' chunk
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
@@ -79,8 +86,8 @@ ScratchLayout scratch_layout(int64_t n)
 }
 
 struct Layout {
-    size_t keys, geom, bin_idx, perm, soa, bounds, partials, scratch, total;
-    int64_t soa_stride, total_bins, cells_per_segment;
+    size_t keys, geom, bin_idx, perm, rec, bounds, partials, scratch, total;
+    int64_t total_bins, cells_per_segment;
 };
 
 // n_bins, d_bin already resolved and validated
@@ -91,14 +98,12 @@ Layout make_layout(int64_t n, int32_t d, int32_t n_segments, int32_t n_bins, int
     for (int c = 0; c < d_bin; ++c) cells *= n_bins;
     L.cells_per_segment = cells;
     L.total_bins = cells * n_segments;
-    L.soa_stride = (n + 63) / 64 * 64;
     size_t off = 0;
     L.keys = off;     off = align_up(off + sizeof(uint32_t) * 2 * (size_t)n_segments * d_bin * kKeyStride);
     L.geom = off;     off = align_up(off + sizeof(float) * kGeomStride * (size_t)n_segments * d_bin);
     L.bin_idx = off;  off = align_up(off + sizeof(int32_t) * (size_t)n);
-    L.perm = off;     off = align_up(off + sizeof(int32_t) * (size_t)n);
-    // d = 3: room for four floats per point, because the backward keeps a padded copy of the rows here
-    L.soa = off;      off = align_up(off + sizeof(float) * (size_t)L.soa_stride * (d == 3 ? 4 : d));
+    L.perm = off;     off = align_up(off + sizeof(int32_t) * (size_t)n);      // the backward's own row order only
+    L.rec = off;      off = align_up(off + sizeof(float) * 4 * (size_t)rec_vecs(d) * (size_t)n);
     L.bounds = off;   off = align_up(off + sizeof(int32_t) * (size_t)(L.total_bins + 1));
     L.partials = off; off = align_up(off + sizeof(int32_t) * (size_t)((L.total_bins + 1 + kScanChunkHost - 1) / kScanChunkHost));
     L.scratch = off;  off = align_up(off + scratch_layout(n).total);
@@ -237,11 +242,10 @@ static fg_status bin_points_impl(const float* coords, const int32_t* row_splits,
     if (((uintptr_t)workspace % kAlign) != 0 || workspace_bytes < L.total) return FG_ERR_WORKSPACE;
     char* ws = (char*)workspace;
     view->bin_idx = (const int32_t*)(ws + L.bin_idx);
-    view->perm = (const int32_t*)(ws + L.perm);
     view->bin_bounds = (const int32_t*)(ws + L.bounds);
-    view->sorted_soa = (const float*)(ws + L.soa);
+    view->sorted_points = (const float*)(ws + L.rec);
     view->seg_geom = (const float*)(ws + L.geom);
-    view->soa_stride = L.soa_stride;
+    view->record_floats = 4 * rec_vecs(d);
     view->cells_per_segment = L.cells_per_segment;
     view->n_bins = n_bins;
     view->d_bin = d_bin;
@@ -249,8 +253,8 @@ static fg_status bin_points_impl(const float* coords, const int32_t* row_splits,
     if (n == 0) return FG_OK;
     hipError_t e = launch_binning(coords, row_splits, (int32_t)n, d, n_segments, n_bins, d_bin, L.total_bins,
                                   (uint32_t*)(ws + L.keys), (float*)(ws + L.geom), (int32_t*)(ws + L.bin_idx),
-                                  (int32_t*)(ws + L.scratch + scratch_layout(n).rank), (int32_t*)(ws + L.perm), (float*)(ws + L.soa),
-                                  L.soa_stride, (int32_t*)(ws + L.bounds), (int32_t*)(ws + L.partials), morton_bits,
+                                  (int32_t*)(ws + L.scratch + scratch_layout(n).rank), (int32_t*)(ws + L.perm), (float*)(ws + L.rec),
+                                  (int32_t*)(ws + L.bounds), (int32_t*)(ws + L.partials), morton_bits,
                                   (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }
@@ -276,21 +280,21 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
     fg_status st = check_problem(n, d, n_segments, k);
     if (st != FG_OK) return st;
     if (n == 0) return FG_OK;
-    if (!row_splits || !out_idx || !out_d2 || !view->perm || !view->bin_bounds || !view->sorted_soa ||
-        !view->seg_geom || !view->scratch)
+    if (!row_splits || !out_idx || !out_d2 || !view->bin_bounds || !view->sorted_points || !view->seg_geom ||
+        !view->scratch)
         return FG_ERR_NULL;
     if (view->d_bin < FG_MIN_D_BIN || view->d_bin > FG_MAX_D_BIN || view->d_bin > d) return FG_ERR_UNSUPPORTED;
     if (view->n_bins < 1 || view->cells_per_segment < 1 ||
-        view->cells_per_segment * (int64_t)n_segments > FG_MAX_TOTAL_BINS || view->soa_stride < n)
+        view->cells_per_segment * (int64_t)n_segments > FG_MAX_TOTAL_BINS || view->record_floats != 4 * rec_vecs(d))
         return FG_ERR_BAD_SHAPE;
     QueryArgs a;
-    a.soa = view->sorted_soa; a.perm = view->perm; a.bounds = view->bin_bounds; a.geom = view->seg_geom;
+    a.rec = reinterpret_cast<const float4*>(view->sorted_points); a.bounds = view->bin_bounds; a.geom = view->seg_geom;
     const ScratchLayout S = scratch_layout(n);
     char* sc = (char*)view->scratch;
     const int32_t* dir = options ? options->dir : nullptr;
-    const int32_t defer = (options && options->defer_lanes >= 0) ? options->defer_lanes : kDefaultDeferLanes;
+    const int32_t defer = (options && options->defer_lanes >= 0) ? options->defer_lanes : default_defer_lanes(d);
     a.row_splits = row_splits; a.dir = dir; a.out_idx = out_idx; a.out_d2 = out_d2; a.out_cand = out_candidates;
-    a.soa_stride = view->soa_stride; a.n = (int32_t)n; a.n_segments = n_segments; a.k = k;
+    a.n = (int32_t)n; a.d = d; a.n_segments = n_segments; a.k = k;
     a.n_bins = view->n_bins; a.cells_per_segment = (int32_t)view->cells_per_segment;
     a.work_list = (int32_t*)(sc + S.work_list); a.work_count = (int32_t*)(sc + S.work_count);
     a.bin_idx = view->bin_idx; a.tile_order = (int32_t*)(sc + S.tile_order);
@@ -405,10 +409,10 @@ fg_status fg_knn_backward(const float* grad_d2, const int32_t* idx, const float*
         st = bin_points_impl(coords, row_splits, n, d, n_segments, 1 << bits, db, bits, workspace, workspace_bytes, &view,
                              stream);
         if (st != FG_OK) return st;
-        perm = view.perm;
-        if (d == 3) coords4 = view.sorted_soa;    // in this mode: the rows padded to four floats, original order
+        perm = (const int32_t*)((const char*)workspace + make_layout(n, d, n_segments, 1 << bits, db).perm);
+        if (d == 3) coords4 = view.sorted_points;    // in this mode: the rows padded to four floats, original order
     }
-    hipError_t e = launch_backward(grad_d2, idx, coords, coords4, perm, (int32_t)n, d, k, grad_coords, (hipStream_t)stream);
+    hipError_t e = launch_backward(grad_d2, idx, coords, coords4, perm, 1, (int32_t)n, d, k, grad_coords, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }
 
@@ -420,11 +424,13 @@ fg_status fg_knn_backward_binned(const fg_binning* view, const float* grad_d2, c
     fg_status st = check_problem(n, d, 1, k);
     if (st != FG_OK) return st;
     if (n == 0) return FG_OK;
-    if (!grad_d2 || !idx || !coords || !grad_coords || !view->perm) return FG_ERR_NULL;
+    if (!grad_d2 || !idx || !coords || !grad_coords || !view->sorted_points) return FG_ERR_NULL;
+    if (view->record_floats != 4 * rec_vecs(d)) return FG_ERR_BAD_SHAPE;
     // the forward's bin order (runs of bins along the last binning dimension) is a little less compact than the
-    // bit-interleaved order fg_knn_backward makes for itself: +0.01 ms in the kernel against 0.08 ms of binning
-    hipError_t e = launch_backward(grad_d2, idx, coords, nullptr, view->perm, (int32_t)n, d, k, grad_coords,
-                                   (hipStream_t)stream);
+    // bit-interleaved order fg_knn_backward makes for itself: +0.01 ms in the kernel against 0.08 ms of binning.
+    // The row of sorted position q is the index field of its point record.
+    hipError_t e = launch_backward(grad_d2, idx, coords, nullptr, reinterpret_cast<const int32_t*>(view->sorted_points) + d,
+                                   view->record_floats, (int32_t)n, d, k, grad_coords, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;
 }
 

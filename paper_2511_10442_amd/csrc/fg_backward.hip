@@ -191,8 +191,8 @@ __device__ __forceinline__ void load_point(const float* __restrict__ coords, con
 template <int D, bool VEC>
 __global__ void __launch_bounds__(bwd_block<D>())
 k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ idx, const float* __restrict__ coords,
-                 const float4* __restrict__ coords4, const int32_t* __restrict__ perm, int32_t n, int32_t k,
-                 float* __restrict__ grad_coords)
+                 const float4* __restrict__ coords4, const int32_t* __restrict__ perm, int32_t perm_stride, int32_t n,
+                 int32_t k, float* __restrict__ grad_coords)
 {
     constexpr int SLOTS = bwd_slots<D>();
     constexpr int ROWS = bwd_rows<D>();
@@ -202,7 +202,7 @@ k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ 
     const int64_t tile0 = (int64_t)blockIdx.x * ROWS;
     for (int i = threadIdx.x; i < SLOTS; i += bwd_block<D>()) keys[i] = -1;
     for (int i = threadIdx.x; i < D * SLOTS; i += bwd_block<D>()) vals[i] = 0.0;
-    for (int i = threadIdx.x; i < ROWS; i += bwd_block<D>()) rows_v[i] = tile0 + i < n ? perm[tile0 + i] : -1;
+    for (int i = threadIdx.x; i < ROWS; i += bwd_block<D>()) rows_v[i] = tile0 + i < n ? perm[(tile0 + i) * perm_stride] : -1;
     __syncthreads();
 
     // A group of 16 lanes owns rows tile0 + sub, tile0 + sub + G, ... (G groups per block); lane l of the
@@ -312,15 +312,16 @@ k_backward_tiled(const float* __restrict__ grad_d2, const int32_t* __restrict__ 
 
 template <int D>
 static void launch_bwd_tiled(const float* grad_d2, const int32_t* idx, const float* coords, const float4* coords4,
-                             const int32_t* perm, int32_t n, int32_t k, float* grad_coords, hipStream_t stream)
+                             const int32_t* perm, int32_t perm_stride, int32_t n, int32_t k, float* grad_coords,
+                             hipStream_t stream)
 {
-    unsigned grid = (unsigned)((n + bwd_rows<D>() - 1) / bwd_rows<D>());
+    unsigned grid = (unsigned)(((int64_t)n + bwd_rows<D>() - 1) / bwd_rows<D>());
     if (((uintptr_t)coords % 16) == 0)
         hipLaunchKernelGGL((k_backward_tiled<D, true>), dim3(grid), dim3(bwd_block<D>()), 0, stream, grad_d2, idx, coords,
-                           coords4, perm, n, k, grad_coords);
+                           coords4, perm, perm_stride, n, k, grad_coords);
     else
         hipLaunchKernelGGL((k_backward_tiled<D, false>), dim3(grid), dim3(bwd_block<D>()), 0, stream, grad_d2, idx, coords,
-                           coords4, perm, n, k, grad_coords);
+                           coords4, perm, perm_stride, n, k, grad_coords);
 }
 
 template <int D>
@@ -333,7 +334,8 @@ static void launch_bwd(const float* grad_d2, const int32_t* idx, const float* co
 }
 
 hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, const float* coords4,
-                           const int32_t* perm, int32_t n, int32_t d, int32_t k, float* grad_coords, hipStream_t stream)
+                           const int32_t* perm, int32_t perm_stride, int32_t n, int32_t d, int32_t k, float* grad_coords,
+                           hipStream_t stream)
 {
     {
         int64_t total = (int64_t)n * d;
@@ -343,15 +345,15 @@ hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float
     }
     if (perm) {
         switch (d) {
-            case 2: launch_bwd_tiled<2>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
-            case 3: launch_bwd_tiled<3>(grad_d2, idx, coords, reinterpret_cast<const float4*>(coords4), perm, n, k, grad_coords, stream); break;
-            case 4: launch_bwd_tiled<4>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
-            case 5: launch_bwd_tiled<5>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
-            case 6: launch_bwd_tiled<6>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
-            case 7: launch_bwd_tiled<7>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
-            case 8: launch_bwd_tiled<8>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
-            case 9: launch_bwd_tiled<9>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
-            case 10: launch_bwd_tiled<10>(grad_d2, idx, coords, nullptr, perm, n, k, grad_coords, stream); break;
+            case 2: launch_bwd_tiled<2>(grad_d2, idx, coords, nullptr, perm, perm_stride, n, k, grad_coords, stream); break;
+            case 3: launch_bwd_tiled<3>(grad_d2, idx, coords, reinterpret_cast<const float4*>(coords4), perm, perm_stride, n, k, grad_coords, stream); break;
+            case 4: launch_bwd_tiled<4>(grad_d2, idx, coords, nullptr, perm, perm_stride, n, k, grad_coords, stream); break;
+            case 5: launch_bwd_tiled<5>(grad_d2, idx, coords, nullptr, perm, perm_stride, n, k, grad_coords, stream); break;
+            case 6: launch_bwd_tiled<6>(grad_d2, idx, coords, nullptr, perm, perm_stride, n, k, grad_coords, stream); break;
+            case 7: launch_bwd_tiled<7>(grad_d2, idx, coords, nullptr, perm, perm_stride, n, k, grad_coords, stream); break;
+            case 8: launch_bwd_tiled<8>(grad_d2, idx, coords, nullptr, perm, perm_stride, n, k, grad_coords, stream); break;
+            case 9: launch_bwd_tiled<9>(grad_d2, idx, coords, nullptr, perm, perm_stride, n, k, grad_coords, stream); break;
+            case 10: launch_bwd_tiled<10>(grad_d2, idx, coords, nullptr, perm, perm_stride, n, k, grad_coords, stream); break;
             default: return hipErrorInvalidValue;
         }
         return hipGetLastError();

@@ -12,8 +12,7 @@ constexpr int kKeyStride = 16;   // words between two bounding-box keys: one 64-
 
 // Everything the query stage needs; plain device pointers.
 struct QueryArgs {
-    const float* soa;          // [d][soa_stride] bin-ordered coordinates
-    const int32_t* perm;       // [n] sorted position -> original row
+    const float4* rec;         // [n][rec_vecs(d)] bin-ordered point records: coordinates, original row, padding
     const int32_t* bounds;     // [S*T+1]
     const float* geom;         // [S][d_bin][4]
     const int32_t* row_splits; // [S+1]
@@ -25,8 +24,8 @@ struct QueryArgs {
     int32_t* work_count;       // [1]
     const int32_t* bin_idx;    // [n] flat bin of each point, original row order
     int32_t* tile_order;       // [2*ceil(n/64) + 128]: tile order, tile classes, class histogram, class cursors
-    int64_t soa_stride;
     int32_t n;
+    int32_t d;                 // coordinates per point (the record length follows from it)
     int32_t n_segments;
     int32_t k;                 // slots per output row
     int32_t slot0;             // tile + list kernels: neighbours already placed by an earlier pass (0 or 64); this pass keeps only keys above the one in row slot `slot0`
@@ -41,27 +40,54 @@ struct QueryArgs {
 hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_t n, int32_t d,
                           int32_t n_segments, int32_t n_bins, int32_t d_bin, int64_t total_bins,
                           uint32_t* bbox_keys, float* geom, int32_t* bin_idx, int32_t* rank,
-                          int32_t* perm, float* soa, int64_t soa_stride, int32_t* bounds,
+                          int32_t* perm, float* rec, int32_t* bounds,
                           int32_t* scan_partials,
-                          int32_t morton_bits /* 0: row-major bins, bin-ordered SoA coordinates written to soa;
+                          int32_t morton_bits /* 0: row-major bins, the bin-ordered point records written to rec (perm unused);
                                                  b > 0 (the backward's row order): n_bins = 2^b, bit-interleaved bin order,
                                                  only perm is written, plus for d = 3 a copy of coords in the original
-                                                 order padded to float4 in place of the SoA */,
+                                                 order padded to float4 in place of the records */,
                           hipStream_t stream);
 
 // d = 2..10, d_bin = 2..min(d,5)
 hipError_t launch_query(const QueryArgs& a, int32_t d, int32_t d_bin, hipStream_t stream);
 
-// perm != nullptr: rows are taken in bin order and combined in LDS; nullptr: plain atomic scatter.
+// perm != nullptr: rows are taken in bin order (row of sorted position q = perm[q * perm_stride]: 1 for a plain
+// permutation, the record length in words for the index field of the forward's point records) and combined in
+// LDS; nullptr: plain atomic scatter.
 // coords4 (d = 3 with perm only, else nullptr): coords padded to four floats per row.
 hipError_t launch_backward(const float* grad_d2, const int32_t* idx, const float* coords, const float* coords4,
-                           const int32_t* perm, int32_t n, int32_t d, int32_t k, float* grad_coords, hipStream_t stream);
+                           const int32_t* perm, int32_t perm_stride, int32_t n, int32_t d, int32_t k, float* grad_coords,
+                           hipStream_t stream);
 
 hipError_t launch_oc_helper(const int32_t* asso_idx, const int32_t* unique_idx, const int32_t* unique_rs_asso,
                             const int32_t* rs, int32_t n_vert, int32_t n_unique, int32_t n_splits, int32_t n_maxuq,
                             int32_t n_maxrs, int32_t calc_m_not, int32_t rot_block, int32_t* M, int32_t* M_not,
                             int32_t* counts /* workspace of oc_workspace_bytes(), or nullptr */, hipStream_t stream);
 size_t oc_workspace_bytes(int64_t n_unique, int32_t n_maxrs);
+
+// A bin-ordered point record: the d coordinates, then the original row index (its bits in a float), then zero
+// padding up to a whole number of 16-byte vectors.  One scattered store per vector in the counting sort, one load
+// per vector wherever a candidate is fetched.
+constexpr int rec_vecs(int d) { return (d + 1 + 3) / 4; }
+template <int D>
+__device__ __forceinline__ void load_rec(const float4* __restrict__ rec, int64_t q, float (&x)[D], int32_t& row)
+{
+    constexpr int NV = rec_vecs(D);
+    float w[NV * 4];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) {
+        const float4 f = rec[q * NV + v];
+        w[4 * v] = f.x; w[4 * v + 1] = f.y; w[4 * v + 2] = f.z; w[4 * v + 3] = f.w;
+    }
+#pragma unroll
+    for (int c = 0; c < D; ++c) x[c] = w[c];
+    row = __float_as_int(w[D]);
+}
+template <int D>
+__device__ __forceinline__ int32_t rec_row(const float4* __restrict__ rec, int64_t q)
+{
+    return __float_as_int(reinterpret_cast<const float*>(rec)[q * (rec_vecs(D) * 4) + D]);
+}
 
 // Direction flags (paper Algorithm 2, useDir / dir[]): 0 or 2 = issues no query, 1 or 2 = is nobody's
 // neighbour, anything else = both roles.

@@ -76,15 +76,15 @@ struct LaneGeom {
         return cannot_improve(mingap * mingap);
     }
 
-    // p: sorted position of the query
-    __device__ __forceinline__ void init_geom(const QueryArgs& a, int32_t p)
+    // p: sorted position of the query; returns its original row
+    __device__ __forceinline__ int32_t init_geom(const QueryArgs& a, int32_t p)
     {
         n_bins = a.n_bins;
         tau = kEmptyKey;
         const int32_t seg = segment_of(a.row_splits, a.n_segments, p);
         seg_cell0 = seg * a.cells_per_segment;
-#pragma unroll
-        for (int c = 0; c < D; ++c) x[c] = a.soa[(int64_t)c * a.soa_stride + p];
+        int32_t row;
+        load_rec<D>(a.rec, p, x, row);
         const float* g = a.geom + (int64_t)seg * DB * kGeomStride;
 #pragma unroll
         for (int c = 0; c < DB; ++c) {
@@ -95,6 +95,7 @@ struct LaneGeom {
             cc[c] = cell_of(x[c], glo[c], inv_w, a.n_bins);
             neff[c] = inv_w > 0.0f ? a.n_bins : 1;
         }
+        return row;
     }
 };
 
@@ -105,12 +106,10 @@ struct ShellSearch : LaneGeom<D, DB> {
     using G::n_bins; using G::seg_cell0; using G::tau;
     using G::cannot_improve; using G::gap; using G::certified;
     uint64_t* heap;   // this lane's column: slot j lives at heap[j * kQueryBlock]
-    const float* __restrict__ soa;
-    const int32_t* __restrict__ perm;
+    const float4* __restrict__ rec;
     const int32_t* __restrict__ bounds;
     const int32_t* __restrict__ dir;
-    int64_t stride;
-    int32_t self_pos, cap, filled, cand;
+    int32_t self_pos, self_row, cap, filled, cand;
 
     __device__ __forceinline__ void sift_down(uint64_t key, int32_t size)
     {
@@ -155,17 +154,19 @@ struct ShellSearch : LaneGeom<D, DB> {
     {
         for (int32_t q = a; q < b; ++q) {
             if (q == self_pos) continue;
-            float diff = x[0] - soa[q];
+            float y[D];
+            int32_t row;
+            load_rec<D>(rec, q, y, row);
+            float diff = x[0] - y[0];
             float d2 = diff * diff;
 #pragma unroll
             for (int c = 1; c < D; ++c) {
-                diff = x[c] - soa[(int64_t)c * stride + q];
+                diff = x[c] - y[c];
                 d2 = d2 + diff * diff;
             }
             if (COUNT) ++cand;
             uint32_t bits = __float_as_uint(d2);
             if (bits > (uint32_t)(tau >> 32)) continue;
-            const int32_t row = perm[q];
             if (dir && !dir_is_neighbour(dir[row])) continue;
             uint64_t key = ((uint64_t)bits << 32) | (uint32_t)row;
             offer(key);
@@ -232,9 +233,9 @@ template <int D, int DB, bool COUNT>
 __device__ __forceinline__ void init_lane(ShellSearch<D, DB, COUNT>& s, const QueryArgs& a, int32_t p, uint64_t* heap)
 {
     s.heap = heap;
-    s.soa = a.soa; s.perm = a.perm; s.bounds = a.bounds; s.dir = a.dir; s.stride = a.soa_stride;
+    s.rec = a.rec; s.bounds = a.bounds; s.dir = a.dir;
     s.self_pos = p; s.cap = a.k - 1; s.filled = 0; s.cand = 0;
-    s.init_geom(a, p);
+    s.self_row = s.init_geom(a, p);
 }
 
 // sort the lane's best list and write its output row (original row order)
@@ -242,7 +243,7 @@ template <int D, int DB, bool COUNT>
 __device__ __forceinline__ void write_row(ShellSearch<D, DB, COUNT>& s, const QueryArgs& a, int32_t p, bool add_count)
 {
     s.sort_ascending();
-    const int32_t row = a.perm[p];
+    const int32_t row = s.self_row;
     int32_t* oi = a.out_idx + (int64_t)row * a.k;
     float* od = a.out_d2 + (int64_t)row * a.k;
     oi[0] = (a.dir && !dir_is_query(a.dir[row])) ? -1 : row;    // a point that asks nothing gets an all-padding row
@@ -316,7 +317,7 @@ k_query_shell(QueryArgs a)
     if (p >= a.n) return;
     ShellSearch<D, DB, COUNT> s;
     init_lane(s, a, p, lds64 + threadIdx.x);
-    if (!(a.dir && !dir_is_query(a.dir[a.perm[p]]))) s.run();
+    if (!(a.dir && !dir_is_query(a.dir[s.self_row]))) s.run();
     write_row(s, a, p, false);
 }
 

@@ -75,7 +75,8 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
         const bool live = t < n_tiles && p < a.n;
         int32_t cc[DB], seg_cell0 = 0;
         {
-            const int32_t b = live ? a.bin_idx[a.perm[p]] : 0;
+            const int32_t row = live ? __float_as_int(reinterpret_cast<const float*>(a.rec)[(int64_t)p * (rec_vecs(a.d) * 4) + a.d]) : 0;
+            const int32_t b = live ? a.bin_idx[row] : 0;
             int32_t r = b % a.cells_per_segment;
             seg_cell0 = b - r;
 #pragma unroll

@@ -75,8 +75,7 @@ k_query_list_wave(QueryArgs a)
     for (int32_t item = blockIdx.x; item < count; item += gridDim.x) {
         const int32_t p = a.work_list[item];
         LaneGeom<D, DB> s;                          // identical in every lane
-        s.init_geom(a, p);
-        const int32_t row = a.perm[p];
+        const int32_t row = s.init_geom(a, p);
         int32_t* oi = a.out_idx + (int64_t)row * a.k;
         float* od = a.out_d2 + (int64_t)row * a.k;
         uint64_t best = 0ull;                       // ascending by lane; low lanes pinned
@@ -190,14 +189,16 @@ k_query_list_wave(QueryArgs a)
                     const int32_t l1 = seg_len1[j];
                     int32_t q = local < l1 ? seg_a1[j] + local : seg_a2[j] + (local - l1);
                     q = in ? q : p;
-                    float diff = s.x[0] - a.soa[q];
+                    float y[D];
+                    int32_t src;
+                    load_rec<D>(a.rec, q, y, src);
+                    float diff = s.x[0] - y[0];
                     float d2 = diff * diff;
 #pragma unroll
                     for (int c = 1; c < D; ++c) {
-                        diff = s.x[c] - a.soa[(int64_t)c * a.soa_stride + q];
+                        diff = s.x[c] - y[c];
                         d2 = d2 + diff * diff;
                     }
-                    const int32_t src = a.perm[q];
                     const bool live = in && q != p && !(a.dir && !dir_is_neighbour(a.dir[src]));
                     const uint64_t key = ((uint64_t)__float_as_uint(d2) << 32) | (uint32_t)src;
                     const bool acc = live && key < s.tau && (a.slot0 == 0 || key > lower);

@@ -136,8 +136,7 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
     const int32_t p = tile * kQueryBlock + lane;
     const bool valid = p < a.n;
     LaneGeom<D, DB> s;
-    s.init_geom(a, valid ? p : a.n - 1);  // dead lanes shadow the last point, never scan or write
-    const int32_t my_row = a.perm[valid ? p : a.n - 1];
+    const int32_t my_row = s.init_geom(a, valid ? p : a.n - 1);  // dead lanes shadow the last point, never scan or write
     const bool asks = !(a.dir && !dir_is_query(a.dir[my_row]));   // direction flag: does this point query at all
     bool active = valid && cap > 0 && asks;
     // second pass of a long list (more than 64 neighbours): the first pass has placed the 64 nearest; only keys
@@ -265,13 +264,14 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
                 const int32_t cnt_pts = PB - base < CHUNK ? PB - base : CHUNK;
                 __syncthreads();
                 for (int32_t i = lane; i < cnt_pts; i += kQueryBlock) {
+                    // the staged form of a point is its record as the counting sort wrote it
                     float w[NV * 4];
 #pragma unroll
-                    for (int c = 0; c < NV * 4; ++c) w[c] = 0.0f;
-#pragma unroll
-                    for (int c = 0; c < D; ++c) w[c] = a.soa[(int64_t)c * a.soa_stride + base + i];
-                    const int32_t src = a.perm[base + i];
-                    w[D] = __int_as_float(src);
+                    for (int v = 0; v < NV; ++v) {
+                        const float4 f = a.rec[(int64_t)(base + i) * NV + v];
+                        w[4 * v] = f.x; w[4 * v + 1] = f.y; w[4 * v + 2] = f.z; w[4 * v + 3] = f.w;
+                    }
+                    const int32_t src = __float_as_int(w[D]);
                     if (a.dir && !dir_is_neighbour(a.dir[src])) {          // never a neighbour: poison its coordinates
 #pragma unroll
                         for (int c = 0; c < D; ++c) w[c] = __uint_as_float(0x7fc00000u);

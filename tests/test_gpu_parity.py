@@ -330,7 +330,7 @@ def test_binning_invariants(d, nb, db):
     perm = bn.perm.cpu().numpy()
     bounds = bn.bin_bounds.cpu().numpy()
     bin_idx = bn.bin_idx.cpu().numpy()
-    soa = bn.sorted_soa.cpu().numpy()
+    rec = bn.sorted_records.cpu().numpy()
     geom = bn.seg_geom.cpu().numpy()
     T = bn.cells_per_segment
     assert sorted(perm.tolist()) == list(range(n))                       # a permutation
@@ -340,7 +340,8 @@ def test_binning_invariants(d, nb, db):
     sorted_bins = bin_idx[perm]
     assert np.all(np.diff(sorted_bins) >= 0)                             # sorted by bin
     assert np.array_equal(np.bincount(bin_idx, minlength=len(bounds) - 1), np.diff(bounds))
-    assert np.array_equal(soa[:, :n].T, x[perm])                         # coordinates moved with their points
+    assert np.array_equal(rec[:, :d], x[perm])                           # coordinates moved with their points
+    assert rec.shape[1] == (d + 1 + 3) // 4 * 4 and np.all(rec[:, d + 1:] == 0.0)
     # the box is the row split's true bounding box; every point's bin is inside its own segment's range
     seg = np.searchsorted(rs[1:], np.arange(n), side="right")
     assert np.all(bin_idx // T == seg)
