@@ -60,6 +60,22 @@ __device__ __forceinline__ int32_t wave_incl_scan_i32(int32_t v, int lane)
 }
 
 constexpr int kListPend = 128;
+constexpr int kListDirect = 12;   // accepted keys of one pass that are inserted one by one instead of sorted
+
+// the key of the last lane, in every lane
+__device__ __forceinline__ uint64_t wave_last_key(uint64_t v)
+{
+    return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), kQueryBlock - 1) << 32) |
+           (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, kQueryBlock - 1);
+}
+
+// value of the lane below (lane 0: zero), 64-bit: a wavefront shift by one lane, no trip through the LDS crossbar
+__device__ __forceinline__ uint64_t wave_from_below(uint64_t v)
+{
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, 0x138, 0xf, 0xf, false);          // wave_shr:1
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), 0x138, 0xf, 0xf, false);
+    return ((uint64_t)hi << 32) | lo;
+}
 
 template <int D, int DB, bool COUNT>
 __global__ void __launch_bounds__(kQueryBlock)
@@ -91,7 +107,7 @@ k_query_list_wave(QueryArgs a)
             lower = li < 0 ? kEmptyKey : (((uint64_t)__float_as_uint(od[a.slot0]) << 32) | (uint32_t)li);
         }
         const int32_t R0 = __float_as_int(od[0]);
-        s.tau = __shfl(best, kQueryBlock - 1, 64);
+        s.tau = wave_last_key(best);
         int32_t npend = 0, cand = 0;
 
         auto absorb64 = [&]() {                     // merges pend[0..min(npend,64)) into the best list
@@ -105,7 +121,7 @@ k_query_list_wave(QueryArgs a)
             const uint64_t rv = __shfl(v, kQueryBlock - 1 - lane, 64);
             best = key_min(rv, best);
             best = wave_merge64(best, lane);
-            s.tau = __shfl(best, kQueryBlock - 1, 64);
+            s.tau = wave_last_key(best);
             __syncthreads();
         };
 
@@ -204,7 +220,24 @@ k_query_list_wave(QueryArgs a)
                     const bool acc = live && key < s.tau && (a.slot0 == 0 || key > lower);
                     if (COUNT) cand += __popcll(__ballot(live));
                     const uint64_t m = __ballot(acc);
-                    if (m) {
+                    if (m && __popcll(m) <= kListDirect) {
+                        // A handed-over query arrives with a k-th best that already prunes most of the shell, so a
+                        // pass rarely keeps more than a few keys.  Those go into the list one at a time: with the
+                        // list ascending by lane, the new list is min(own, max(key, the lane below's)) in every
+                        // lane (keys below the new one stay, the new one lands in the first lane holding a larger
+                        // key, every larger key moves one lane up and the largest leaves): five instructions per
+                        // key against some three hundred for a sorted merge of the pending array, and the k-th
+                        // best tightens at once.  A key that no longer beats the k-th best changes nothing.
+                        uint64_t mm = m;
+                        do {
+                            const int b = __ffsll((unsigned long long)mm) - 1;
+                            mm &= mm - 1;
+                            const uint64_t x = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(key >> 32), b) << 32) |
+                                               (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)key, b);
+                            best = key_min(best, key_max(x, wave_from_below(best)));
+                        } while (mm);
+                        s.tau = wave_last_key(best);
+                    } else if (m) {
                         if (acc) pend[npend + __popcll(m & lt_mask)] = key;
                         npend += __popcll(m);
                         __syncthreads();
