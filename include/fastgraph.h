@@ -78,19 +78,25 @@ fg_status fg_workspace_size(int64_t n, int32_t d, int32_t n_segments, int32_t k,
 
 /* Result of the binning stage: device pointers into the caller's workspace. */
 typedef struct {
-    const int32_t* bin_idx;    /* [n]  flat bin of each point, ORIGINAL order; segment s owns bins [s*T, (s+1)*T); inside
-                                  a segment the bins are numbered row-major over the grid, last binning dimension
-                                  fastest (the flattening of Algorithm 1) */
-    const int32_t* bin_bounds; /* [n_segments*T + 1] exclusive prefix of bin populations: bin b holds
-                                  sorted positions [bin_bounds[b], bin_bounds[b+1]) */
+    const int32_t* bin_idx;    /* [n]  flat cell of each point, ORIGINAL order; segment s owns cells [s*T, (s+1)*T);
+                                  inside a segment the cells are numbered row-major over the grid, last binning
+                                  dimension fastest (the flattening of Algorithm 1).  A cell is a bin, or, with
+                                  sub_bins > 1, one of the sub_bins equal slices every bin is cut into along the last
+                                  binning dimension (that dimension then counts n_bins * sub_bins cells; bin b of the
+                                  plain numbering is cells [b*sub_bins, (b+1)*sub_bins)) */
+    const int32_t* bin_bounds; /* [n_segments*T + 1] exclusive prefix of cell populations: cell c holds
+                                  sorted positions [bin_bounds[c], bin_bounds[c+1]) */
     const float* sorted_points;/* [n][record_floats] the points in bin order, one record each: the d coordinates, then
                                   the original row index (an int32 stored in the float's 4 bytes), then zeros.  The
                                   index fields, read in order, are the permutation sorted position -> original row */
-    const float* seg_geom;     /* [n_segments][d_bin][4]: lower box edge, bins per unit length (0 if the
-                                  segment has zero extent in that dimension), bin width, rounding slack */
-    int64_t cells_per_segment; /* T = n_bins^d_bin */
+    const float* seg_geom;     /* [n_segments][d_bin][4]: lower box edge, cells per unit length (0 if the
+                                  segment has zero extent in that dimension), cell width, rounding slack */
+    int64_t cells_per_segment; /* T = n_bins^d_bin * sub_bins */
     int32_t n_bins;            /* bins per binning dimension actually used */
     int32_t d_bin;             /* binning dimensions actually used (the first d_bin coordinates) */
+    int32_t sub_bins;          /* slices per bin along the last binning dimension: 1, 2 or 4, chosen by fg_bin_points
+                                  (the search prunes by slice inside the runs of bins it scans; the result does not
+                                  depend on it) */
     int32_t record_floats;     /* floats per record of sorted_points: d + 1 rounded up to a multiple of 4 */
     void* scratch;             /* opaque: scratch of the query stage inside the workspace.  Its first int32 holds, after
                                   fg_query_binned, the number of queries the tile kernel handed to the list kernel (a

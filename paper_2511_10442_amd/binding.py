@@ -37,7 +37,8 @@ class _Binning(ctypes.Structure):
     _fields_ = [("bin_idx", ctypes.c_void_p), ("bin_bounds", ctypes.c_void_p),
                 ("sorted_points", ctypes.c_void_p), ("seg_geom", ctypes.c_void_p),
                 ("cells_per_segment", ctypes.c_int64), ("n_bins", ctypes.c_int32),
-                ("d_bin", ctypes.c_int32), ("record_floats", ctypes.c_int32), ("scratch", ctypes.c_void_p)]
+                ("d_bin", ctypes.c_int32), ("sub_bins", ctypes.c_int32), ("record_floats", ctypes.c_int32),
+                ("scratch", ctypes.c_void_p)]
 
 
 class _QueryOptions(ctypes.Structure):
@@ -149,6 +150,7 @@ class Binning:
     d_bin: int
     cells_per_segment: int
     record_floats: int
+    sub_bins: int
 
     def _view(self, ptr: int, count: int, dtype) -> torch.Tensor:
         off = ptr - self.workspace.data_ptr()
@@ -203,7 +205,7 @@ def fg_bin_points(coords: torch.Tensor, row_splits: torch.Tensor, k_hint: int, n
                                _ptr(workspace), workspace.numel(), ctypes.byref(raw), _stream()),
            "fg_bin_points")
     return Binning(raw, workspace, n, d, s, int(raw.n_bins), int(raw.d_bin),
-                   int(raw.cells_per_segment), int(raw.record_floats))
+                   int(raw.cells_per_segment), int(raw.record_floats), int(raw.sub_bins))
 
 
 def _out(t, shape, dtype, device, name: str) -> torch.Tensor:

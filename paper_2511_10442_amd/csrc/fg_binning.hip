@@ -169,7 +169,7 @@ constexpr int kAssignProbes = 8;
 template <int DB>
 __global__ void __launch_bounds__(kBlock)
 k_assign(const float* __restrict__ coords, const int32_t* __restrict__ row_splits, int32_t n, int32_t d,
-         int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, int32_t morton_bits,
+         int32_t n_segments, int32_t n_bins, int32_t sub_shift, int32_t cells_per_segment, int32_t morton_bits,
          const uint32_t* __restrict__ bbox_keys, float* __restrict__ geom, int32_t* __restrict__ bin_idx,
          int32_t* __restrict__ rank, int32_t* __restrict__ counters)
 {
@@ -177,7 +177,7 @@ k_assign(const float* __restrict__ coords, const int32_t* __restrict__ row_split
     // computed from the same bounding-box keys with the same arithmetic
     const int32_t n_keys = n_segments * DB;
     for (int32_t t = blockIdx.x * kBlock + threadIdx.x; t < n_keys; t += gridDim.x * kBlock) {
-        const DimGeom r = dim_geometry(bbox_keys, n_keys, t, n_bins);
+        const DimGeom r = dim_geometry(bbox_keys, n_keys, t, (t % DB == DB - 1) ? n_bins << sub_shift : n_bins);
         float* g = geom + (int64_t)t * kGeomStride;
         g[0] = r.lo; g[1] = r.inv_w; g[2] = r.w; g[3] = r.slack;
     }
@@ -196,13 +196,14 @@ k_assign(const float* __restrict__ coords, const int32_t* __restrict__ row_split
         int32_t cell[DB];
 #pragma unroll
         for (int c = 0; c < DB; ++c) {
-            const DimGeom r = dim_geometry(bbox_keys, n_keys, s * DB + c, n_bins);
-            cell[c] = cell_of(p[c], r.lo, r.inv_w, n_bins);
+            const int32_t nb_c = (c == DB - 1) ? n_bins << sub_shift : n_bins;    // the last dimension counts slices
+            const DimGeom r = dim_geometry(bbox_keys, n_keys, s * DB + c, nb_c);
+            cell[c] = cell_of(p[c], r.lo, r.inv_w, nb_c);
         }
         int32_t f = 0;
         if (morton_bits == 0) {                 // row-major, last dimension fastest (what the query kernels expect)
 #pragma unroll
-            for (int c = 0; c < DB; ++c) f = f * n_bins + cell[c];
+            for (int c = 0; c < DB; ++c) f = f * ((c == DB - 1) ? n_bins << sub_shift : n_bins) + cell[c];
         } else {                                // bit-interleaved: consecutive bins form compact blocks in space
             for (int b = 0; b < morton_bits; ++b) {
 #pragma unroll
@@ -364,8 +365,8 @@ k_scatter(const float* __restrict__ coords, int32_t n, const int32_t* __restrict
 
 template <int DB>
 static void launch_bbox_assign(bool assign, const float* coords, const int32_t* row_splits, int32_t n, int32_t d,
-                               int32_t n_segments, int32_t n_bins, int32_t cells_per_segment, int32_t morton_bits,
-                               uint32_t* bbox_keys,
+                               int32_t n_segments, int32_t n_bins, int32_t sub_shift, int32_t cells_per_segment,
+                               int32_t morton_bits, uint32_t* bbox_keys,
                                float* geom, int32_t* bin_idx, int32_t* rank, int32_t* counters,
                                hipStream_t stream)
 {
@@ -374,7 +375,7 @@ static void launch_bbox_assign(bool assign, const float* coords, const int32_t* 
                            row_splits, n, d, n_segments, bbox_keys);
     else
         hipLaunchKernelGGL(k_assign<DB>, dim3((unsigned)(((int64_t)n + kAssignChunk - 1) / kAssignChunk)), dim3(kBlock), 0, stream, coords,
-                           row_splits, n, d, n_segments, n_bins, cells_per_segment, morton_bits, bbox_keys, geom,
+                           row_splits, n, d, n_segments, n_bins, sub_shift, cells_per_segment, morton_bits, bbox_keys, geom,
                            bin_idx, rank, counters);
 }
 
@@ -392,7 +393,7 @@ static void launch_scatter(bool rows_only, const float* coords, int32_t n, const
 }
 
 hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_t n, int32_t d,
-                          int32_t n_segments, int32_t n_bins, int32_t d_bin, int64_t total_bins,
+                          int32_t n_segments, int32_t n_bins, int32_t d_bin, int32_t sub_shift, int64_t total_bins,
                           uint32_t* bbox_keys, float* geom, int32_t* bin_idx, int32_t* rank,
                           int32_t* perm, float* rec, int32_t* bounds,
                           int32_t* scan_partials, int32_t morton_bits, hipStream_t stream)
@@ -409,13 +410,13 @@ hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_
     }
 #define FG_DB_SWITCH(ASSIGN)                                                                                       \
     switch (d_bin) {                                                                                               \
-        case 2: launch_bbox_assign<2>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
+        case 2: launch_bbox_assign<2>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, sub_shift, cells_per_segment, \
                                       morton_bits, bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
-        case 3: launch_bbox_assign<3>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
+        case 3: launch_bbox_assign<3>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, sub_shift, cells_per_segment, \
                                       morton_bits, bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
-        case 4: launch_bbox_assign<4>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
+        case 4: launch_bbox_assign<4>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, sub_shift, cells_per_segment, \
                                       morton_bits, bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
-        case 5: launch_bbox_assign<5>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, cells_per_segment,     \
+        case 5: launch_bbox_assign<5>(ASSIGN, coords, row_splits, n, d, n_segments, n_bins, sub_shift, cells_per_segment, \
                                       morton_bits, bbox_keys, geom, bin_idx, rank, bounds, stream); break;                      \
         default: return hipErrorInvalidValue;                                                                      \
     }

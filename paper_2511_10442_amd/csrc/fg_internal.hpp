@@ -13,7 +13,7 @@ constexpr int kKeyStride = 16;   // words between two bounding-box keys: one 64-
 // Everything the query stage needs; plain device pointers.
 struct QueryArgs {
     const float4* rec;         // [n][rec_vecs(d)] bin-ordered point records: coordinates, original row, padding
-    const int32_t* bounds;     // [S*T+1]
+    const int32_t* bounds;     // [S*T+1], T counted in slices (see sub_shift)
     const float* geom;         // [S][d_bin][4]
     const int32_t* row_splits; // [S+1]
     const int32_t* dir;        // [n] direction flags in ORIGINAL row order, or nullptr
@@ -31,14 +31,16 @@ struct QueryArgs {
     int32_t slot0;             // tile + list kernels: neighbours already placed by an earlier pass (0 or 64); this pass keeps only keys above the one in row slot `slot0`
     int32_t k_list;            // tile + list kernels: neighbours this pass finds (1..64, or 0 for K = 1); they go to row slots slot0+1 .. slot0+k_list
     int32_t n_bins;
-    int32_t cells_per_segment;
+    int32_t cells_per_segment; // T: bins of a row split times the slices per bin
+    int32_t sub_shift;         // log2 of the slices every bin is cut into along the last binning dimension
     int32_t algo;              // 0: tile kernel + list kernel, 1: one lane per query for everything, 2: as 0 with the flattened scan on every tile
     int32_t defer_lanes;       // tile kernel: go on past shell 1 only while more lanes than this are unfinished
 };
 
 // Host-side launchers, one per translation unit.  Each returns hipGetLastError() of its launches.
 hipError_t launch_binning(const float* coords, const int32_t* row_splits, int32_t n, int32_t d,
-                          int32_t n_segments, int32_t n_bins, int32_t d_bin, int64_t total_bins,
+                          int32_t n_segments, int32_t n_bins, int32_t d_bin, int32_t sub_shift /* last binning dimension:
+                          n_bins << sub_shift slices */, int64_t total_bins,
                           uint32_t* bbox_keys, float* geom, int32_t* bin_idx, int32_t* rank,
                           int32_t* perm, float* rec, int32_t* bounds,
                           int32_t* scan_partials,

@@ -34,7 +34,25 @@ struct LaneGeom {
     float glo[DB], gw[DB], gslack[DB];
     int32_t cc[DB], neff[DB];
     int32_t n_bins, seg_cell0;
+    // The last binning dimension is cut finer than the others: every bin into 2^sub_shift slices, which are what
+    // the counting sort orders by and what the bin boundaries count.  Shells, gaps and the stop test work in
+    // whole bins (cc, neff; bin j starts at slice j << sub_shift); glo/gw/gslack of that dimension describe the
+    // slices, slice_inv_w is slices per unit length and my_slice the query's own slice.
+    int32_t sub_shift;
+    float slice_inv_w;
     uint64_t tau;
+
+    // lower edge of bin j in dimension c
+    __device__ __forceinline__ float edge(int c, int32_t j) const
+    {
+        return glo[c] + (float)(c == DB - 1 ? j << sub_shift : j) * gw[c];
+    }
+    // first entry of the bin boundaries for bin z of the last dimension in the column of bins `col` (flat over
+    // the first DB-1 dimensions)
+    __device__ __forceinline__ int32_t bounds_at(int32_t col, int32_t z) const
+    {
+        return seg_cell0 + ((col * n_bins + z) << sub_shift);
+    }
 
     __device__ __forceinline__ float tau_d2() const { return __uint_as_float((uint32_t)(tau >> 32)); }
 
@@ -48,9 +66,45 @@ struct LaneGeom {
     __device__ __forceinline__ float gap(int c, int32_t j, int32_t o) const
     {
         if (o == 0) return 0.0f;
-        float g = (o > 0) ? (glo[c] + (float)j * gw[c]) - x[c] : x[c] - (glo[c] + (float)(j + 1) * gw[c]);
+        float g = (o > 0) ? edge(c, j) - x[c] : x[c] - edge(c, j + 1);
         g -= gslack[c];
         return g > 0.0f ? g : 0.0f;
+    }
+
+    // The slices [lo_s, hi_s] of the last binning dimension that can still hold a point entering the best list,
+    // for a column of bins whose squared lower-bound distance in the other binning dimensions is `partial`.
+    // The ends are guessed from the radius the k-th best leaves in this dimension and then checked with the same
+    // bound that prunes whole bins (slices below lo_s lie under the lower edge of slice lo_s, farther than the
+    // gap to that edge); a guess that fails the check moves out by one slice, then gives way to the full range.
+    __device__ __forceinline__ void slice_reach(float partial, int32_t& lo_s, int32_t& hi_s) const
+    {
+        constexpr int c = DB - 1;
+        const int32_t n_slices = n_bins << sub_shift;
+        lo_s = 0;
+        hi_s = n_slices - 1;
+        if (tau >= kEmptyKey) return;
+        const float left = tau_d2() - partial;
+        const float r = sqrtf(left > 0.0f ? left : 0.0f);
+        auto below_out = [&](int32_t j) {       // true: no slice under j can improve the list
+            const float g = x[c] - (glo[c] + (float)j * gw[c]) - gslack[c];
+            return g > 0.0f && cannot_improve(partial + g * g);
+        };
+        auto above_out = [&](int32_t j) {       // true: no slice over j can improve the list
+            const float g = (glo[c] + (float)(j + 1) * gw[c]) - x[c] - gslack[c];
+            return g > 0.0f && cannot_improve(partial + g * g);
+        };
+        int32_t jl = cell_of(x[c] - r, glo[c], slice_inv_w, n_slices);
+        if (jl > 0 && !below_out(jl)) {
+            --jl;
+            if (jl > 0 && !below_out(jl)) jl = 0;
+        }
+        int32_t jh = cell_of(x[c] + r, glo[c], slice_inv_w, n_slices);
+        if (jh < n_slices - 1 && !above_out(jh)) {
+            ++jh;
+            if (jh < n_slices - 1 && !above_out(jh)) jh = n_slices - 1;
+        }
+        lo_s = jl;
+        hi_s = jh;
     }
 
     // after shell r: true when the search may stop
@@ -63,12 +117,12 @@ struct LaneGeom {
             int32_t jl = cc[c] - r, jh = cc[c] + r;
             if (jl > 0) {
                 covered = false;
-                float g = x[c] - (glo[c] + (float)jl * gw[c]) - gslack[c];
+                float g = x[c] - edge(c, jl) - gslack[c];
                 mingap = fminf(mingap, g > 0.0f ? g : 0.0f);
             }
             if (jh < neff[c] - 1) {
                 covered = false;
-                float g = (glo[c] + (float)(jh + 1) * gw[c]) - x[c] - gslack[c];
+                float g = edge(c, jh + 1) - x[c] - gslack[c];
                 mingap = fminf(mingap, g > 0.0f ? g : 0.0f);
             }
         }
@@ -80,6 +134,7 @@ struct LaneGeom {
     __device__ __forceinline__ int32_t init_geom(const QueryArgs& a, int32_t p)
     {
         n_bins = a.n_bins;
+        sub_shift = a.sub_shift;
         tau = kEmptyKey;
         const int32_t seg = segment_of(a.row_splits, a.n_segments, p);
         seg_cell0 = seg * a.cells_per_segment;
@@ -92,7 +147,12 @@ struct LaneGeom {
             glo[c] = g[c * kGeomStride + 0];
             gw[c] = g[c * kGeomStride + 2];
             gslack[c] = g[c * kGeomStride + 3];
-            cc[c] = cell_of(x[c], glo[c], inv_w, a.n_bins);
+            if (c == DB - 1) {
+                cc[c] = cell_of(x[c], glo[c], inv_w, a.n_bins << a.sub_shift) >> a.sub_shift;
+                slice_inv_w = inv_w;
+            } else {
+                cc[c] = cell_of(x[c], glo[c], inv_w, a.n_bins);
+            }
             neff[c] = inv_w > 0.0f ? a.n_bins : 1;
         }
         return row;
@@ -103,7 +163,7 @@ template <int D, int DB, bool COUNT>
 struct ShellSearch : LaneGeom<D, DB> {
     using G = LaneGeom<D, DB>;
     using G::x; using G::glo; using G::gw; using G::gslack; using G::cc; using G::neff;
-    using G::n_bins; using G::seg_cell0; using G::tau;
+    using G::n_bins; using G::seg_cell0; using G::tau; using G::bounds_at;
     using G::cannot_improve; using G::gap; using G::certified;
     uint64_t* heap;   // this lane's column: slot j lives at heap[j * kQueryBlock]
     const float4* __restrict__ rec;
@@ -188,19 +248,18 @@ struct ShellSearch : LaneGeom<D, DB> {
                 visit<LVL + 1>(r, flat * n_bins + c0 + o, p2, on);
             }
         } else {
-            const int32_t row = seg_cell0 + flat * n_bins;
             if (surf) {   // the whole run of the last dimension belongs to this shell
                 int32_t za = c0 - r < 0 ? 0 : c0 - r;
                 int32_t zb = c0 + r > neff[LVL] - 1 ? neff[LVL] - 1 : c0 + r;
-                scan_points(bounds[row + za], bounds[row + zb + 1]);
+                scan_points(bounds[bounds_at(flat, za)], bounds[bounds_at(flat, zb + 1)]);
             } else {      // only the two end bins of the run are on the surface
                 if (c0 - r >= 0) {
                     float g = gap(LVL, c0 - r, -r);
-                    if (!cannot_improve(partial + g * g)) scan_points(bounds[row + c0 - r], bounds[row + c0 - r + 1]);
+                    if (!cannot_improve(partial + g * g)) scan_points(bounds[bounds_at(flat, c0 - r)], bounds[bounds_at(flat, c0 - r + 1)]);
                 }
                 if (c0 + r <= neff[LVL] - 1) {
                     float g = gap(LVL, c0 + r, r);
-                    if (!cannot_improve(partial + g * g)) scan_points(bounds[row + c0 + r], bounds[row + c0 + r + 1]);
+                    if (!cannot_improve(partial + g * g)) scan_points(bounds[bounds_at(flat, c0 + r)], bounds[bounds_at(flat, c0 + r + 1)]);
                 }
             }
         }

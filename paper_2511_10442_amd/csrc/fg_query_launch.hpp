@@ -79,8 +79,12 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
             const int32_t b = live ? a.bin_idx[row] : 0;
             int32_t r = b % a.cells_per_segment;
             seg_cell0 = b - r;
+            // the flat number counts slices of the last dimension (2^sub_shift per bin)
+            const int32_t nz = a.n_bins << a.sub_shift;
+            cc[DB - 1] = (r % nz) >> a.sub_shift;
+            r /= nz;
 #pragma unroll
-            for (int c = DB - 1; c >= 0; --c) { cc[c] = r % a.n_bins; r /= a.n_bins; }
+            for (int c = DB - 2; c >= 0; --c) { cc[c] = r % a.n_bins; r /= a.n_bins; }
         }
         int32_t work = 0, around = 0, longest = 0, total = 0;
         for (int32_t col = 0; col < ncols; ++col) {
@@ -97,8 +101,8 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
             if (ok) {
                 const int32_t cz = cc[DB - 1];
                 const int32_t za = cz > 0 ? cz - 1 : 0, zb = cz < a.n_bins - 1 ? cz + 1 : a.n_bins - 1;
-                const int32_t row = seg_cell0 + flat * a.n_bins;
-                len = a.bounds[row + zb + 1] - a.bounds[row + za];
+                const int32_t row = flat * a.n_bins;
+                len = a.bounds[seg_cell0 + ((row + zb + 1) << a.sub_shift)] - a.bounds[seg_cell0 + ((row + za) << a.sub_shift)];
             }
             around += len;
             const int32_t col_max = oct_max_i32(len);
@@ -130,8 +134,8 @@ static __global__ void __launch_bounds__(256) k_tile_work(QueryArgs a, int32_t n
                 if (ok) {
                     const int32_t cz = cc[DB - 1];
                     const int32_t za = cz > 1 ? cz - 2 : 0, zb = cz < a.n_bins - 2 ? cz + 2 : a.n_bins - 1;
-                    const int32_t row = seg_cell0 + flat * a.n_bins;
-                    len = a.bounds[row + zb + 1] - a.bounds[row + za];
+                    const int32_t row = flat * a.n_bins;
+                    len = a.bounds[seg_cell0 + ((row + zb + 1) << a.sub_shift)] - a.bounds[seg_cell0 + ((row + za) << a.sub_shift)];
                 }
                 work += oct_max_i32(len) >> 2;
             }

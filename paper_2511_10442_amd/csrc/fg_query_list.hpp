@@ -160,7 +160,6 @@ k_query_list_wave(QueryArgs a)
                 int32_t a1 = 0, b1 = 0, a2 = 0, b2 = 0;
                 if (ok) {
                     const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
-                    const int32_t row = s.seg_cell0 + flat * a.n_bins;
                     if (surf) {
                         int32_t za = cz - R < 0 ? 0 : cz - R;
                         int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
@@ -174,16 +173,16 @@ k_query_list_wave(QueryArgs a)
                             if (!s.cannot_improve(partial + g * g)) break;
                             --zb;
                         }
-                        a1 = a.bounds[row + za];
-                        b1 = a.bounds[row + zb + 1];
+                        a1 = a.bounds[s.bounds_at(flat, za)];
+                        b1 = a.bounds[s.bounds_at(flat, zb + 1)];
                     } else {
                         if (cz - R >= 0) {
                             const float g = s.gap(DB - 1, cz - R, -R);
-                            if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[row + cz - R]; b1 = a.bounds[row + cz - R + 1]; }
+                            if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[s.bounds_at(flat, cz - R)]; b1 = a.bounds[s.bounds_at(flat, cz - R + 1)]; }
                         }
                         if (cz + R <= nz - 1) {
                             const float g = s.gap(DB - 1, cz + R, R);
-                            if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[row + cz + R]; b2 = a.bounds[row + cz + R + 1]; }
+                            if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[s.bounds_at(flat, cz + R)]; b2 = a.bounds[s.bounds_at(flat, cz + R + 1)]; }
                         }
                     }
                 }

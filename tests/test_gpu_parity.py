@@ -350,8 +350,10 @@ def test_binning_invariants(d, nb, db):
             assert np.array_equal(geom[s, :, 0], x[rs[s]:rs[s + 1], :bn.d_bin].min(axis=0))
     # bins are monotone in every binned coordinate (what the search's lower bounds rely on)
     local = bin_idx - seg * T
+    assert T == bn.n_bins ** bn.d_bin * bn.sub_bins and bn.sub_bins in (1, 2, 4)
+    last = bn.n_bins * bn.sub_bins                                        # cells along the last binning dimension
     for c in range(bn.d_bin):
-        cell_c = (local // (bn.n_bins ** (bn.d_bin - 1 - c))) % bn.n_bins
+        cell_c = local % last if c == bn.d_bin - 1 else (local // (last * bn.n_bins ** (bn.d_bin - 2 - c))) % bn.n_bins
         for s, size in enumerate(sizes):
             if size > 1:
                 sl = slice(rs[s], rs[s + 1])

@@ -117,11 +117,16 @@ def test_argument_validation_without_gpu():
 def test_workspace_size_scales_linearly():
     # (the size also covers the grid fg_knn_backward bins its rows with: a power of two near the automatic
     #  bin count, so compare sizes whose explicit grid is the larger of the two)
-    a = B.fg_workspace_size(100_000, 3, 1, 16, 40, 3)
-    b = B.fg_workspace_size(200_000, 3, 1, 16, 40, 3)
+    a = B.fg_workspace_size(100_000, 3, 1, 16, 24, 3)
+    b = B.fg_workspace_size(200_000, 3, 1, 16, 24, 3)
     # per point: bin_idx + rank + perm + work list + coordinates (d = 3 is given room for four) = 8 words,
     # plus two words per tile of 64 points for the tile order
     assert abs((b - a) - 100_000 * 4 * (8 + 2 / 64)) < 4096
-    c = B.fg_workspace_size(100_000, 3, 1, 16, 60, 3)
-    assert abs((c - a) - (60 ** 3 - 40 ** 3) * 4) < 8192
+    # per bin: one word for each of the four slices it is cut into along the last binning dimension (grids
+    # well below the number of points; coarser cuts are chosen for larger ones)
+    c = B.fg_workspace_size(100_000, 3, 1, 16, 34, 3)
+    assert abs((c - a) - (34 ** 3 - 24 ** 3) * 4 * 4) < 8192
+    # a table of four slices per bin would exceed twice the number of points: two slices
+    e = B.fg_workspace_size(100_000, 3, 1, 16, 40, 3)
+    assert abs((e - a) - (2 * 40 ** 3 - 4 * 24 ** 3) * 4) < 8192
     assert B.fg_workspace_size(0, 3, 1, 16) >= 0
