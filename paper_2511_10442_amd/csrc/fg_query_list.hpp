@@ -160,6 +160,16 @@ k_query_list_wave(QueryArgs a)
                 int32_t a1 = 0, b1 = 0, a2 = 0, b2 = 0;
                 if (ok) {
                     const int32_t cz = s.cc[DB - 1], nz = s.neff[DB - 1];
+                    // every run ends at the slice of its bins that the k-th best still reaches
+                    const int32_t sh = a.sub_shift;
+                    const int32_t row0 = s.bounds_at(flat, 0);
+                    int32_t s_lo = 0, s_hi = 0x7ffffffe;
+                    if (sh > 0) s.slice_reach(partial, s_lo, s_hi);
+                    auto cut_run = [&](int32_t z_first, int32_t z_last, int32_t& from, int32_t& to) {   // bins, inclusive
+                        const int32_t fa = (z_first << sh) > s_lo ? (z_first << sh) : s_lo;
+                        const int32_t fb = ((z_last + 1) << sh) < s_hi + 1 ? ((z_last + 1) << sh) : s_hi + 1;
+                        if (fb > fa) { from = a.bounds[row0 + fa]; to = a.bounds[row0 + fb]; }
+                    };
                     if (surf) {
                         int32_t za = cz - R < 0 ? 0 : cz - R;
                         int32_t zb = cz + R > nz - 1 ? nz - 1 : cz + R;
@@ -173,16 +183,15 @@ k_query_list_wave(QueryArgs a)
                             if (!s.cannot_improve(partial + g * g)) break;
                             --zb;
                         }
-                        a1 = a.bounds[s.bounds_at(flat, za)];
-                        b1 = a.bounds[s.bounds_at(flat, zb + 1)];
+                        cut_run(za, zb, a1, b1);
                     } else {
                         if (cz - R >= 0) {
                             const float g = s.gap(DB - 1, cz - R, -R);
-                            if (!s.cannot_improve(partial + g * g)) { a1 = a.bounds[s.bounds_at(flat, cz - R)]; b1 = a.bounds[s.bounds_at(flat, cz - R + 1)]; }
+                            if (!s.cannot_improve(partial + g * g)) cut_run(cz - R, cz - R, a1, b1);
                         }
                         if (cz + R <= nz - 1) {
                             const float g = s.gap(DB - 1, cz + R, R);
-                            if (!s.cannot_improve(partial + g * g)) { a2 = a.bounds[s.bounds_at(flat, cz + R)]; b2 = a.bounds[s.bounds_at(flat, cz + R + 1)]; }
+                            if (!s.cannot_improve(partial + g * g)) cut_run(cz + R, cz + R, a2, b2);
                         }
                     }
                 }
