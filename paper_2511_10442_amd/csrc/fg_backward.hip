@@ -80,24 +80,15 @@ __device__ __forceinline__ float row16_sum_to_last(float v)
 // entry in the first probing round; with four slots per row the larger tile saved memory-side requests in
 // the flush but lost more in probing rounds: 0.378 against 0.355 ms).
 constexpr int kBwdProbes = 12;
-#ifndef FG_BWD_BATCH
-#define FG_BWD_BATCH 4
-#endif
-constexpr int kBwdBatch = FG_BWD_BATCH;   // (row, piece) pairs in flight per lane
-#ifndef FG_BWD_THREADS
-#define FG_BWD_THREADS 1024
-#endif
-template <int D> constexpr int bwd_block() { return FG_BWD_THREADS; }
-#ifndef FG_BWD_LDS_KB
-#define FG_BWD_LDS_KB 56
-#endif
+constexpr int kBwdBatch = 4;          // (row, piece) pairs in flight per lane
+constexpr int kBwdThreads = 1024;
+constexpr int kBwdLdsKb = 56;         // LDS budget of a block's table: two blocks per CU
+constexpr int kBwdSlotsPerRow = 8;
+template <int D> constexpr int bwd_block() { return kBwdThreads; }
 constexpr int pow2_floor(int v) { int p = 1; while (2 * p <= v) p *= 2; return p; }
 // table slots: the largest power of two whose keys (4 bytes) and D double sums fit the LDS budget of a block
-template <int D> constexpr int bwd_slots() { return pow2_floor(FG_BWD_LDS_KB * 1024 / (4 + 8 * D)); }
-#ifndef FG_BWD_ROWS_DIV
-#define FG_BWD_ROWS_DIV 8
-#endif
-template <int D> constexpr int bwd_rows() { return bwd_slots<D>() / FG_BWD_ROWS_DIV; }
+template <int D> constexpr int bwd_slots() { return pow2_floor(kBwdLdsKb * 1024 / (4 + 8 * D)); }
+template <int D> constexpr int bwd_rows() { return bwd_slots<D>() / kBwdSlotsPerRow; }
 constexpr int ilog2(int v) { int b = 0; while ((1 << b) < v) ++b; return b; }
 
 // Adds NE entries of one lane to the table (key u[e], D values each; u[e] < 0: nothing to add).

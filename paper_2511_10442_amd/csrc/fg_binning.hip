@@ -5,14 +5,17 @@
 //   prepare   zero the bin counters, reset the bounding-box keys
 //   bbox      per row split, min/max of the first d_bin coordinates (register, wave and block
 //             reduction, one atomic pair per block and dimension on an order-preserving key)
-//   assign    per (row split, dim) the grid geometry (lower edge, bins per unit length, bin width,
+//   assign    per (row split, dim) the grid geometry (lower edge, cells per unit length, cell width,
 //             rounding slack: computed from the bounding box where needed, the records written
-//             for the query kernels); flat bin of every point + its arrival rank inside the bin
-//             (LDS-privatised histogram per block, one returning global atomic per distinct bin
-//             and block)
+//             for the query kernels); flat cell of every point + its arrival rank inside the cell
+//             (LDS-privatised histogram per block, one returning global atomic per distinct cell
+//             and block; issuing a thread's atomics back to back instead of one round trip at a
+//             time changed nothing: the kernel runs at the rate of the memory-side atomics).
+//             A cell is a bin, or one of the 2^sub_shift slices a bin is cut into along the last
+//             binning dimension
 //   scan      exclusive prefix over the counters (per-chunk totals, then apply; a pass over the
 //             totals in between only when there are many chunks)
-//   scatter   sorted position = bounds[bin] + rank: write perm and the bin-ordered SoA coords
+//   scatter   sorted position = bounds[cell] + rank: one record per point (coordinates, original row)
 #include "fg_internal.hpp"
 
 namespace fg {

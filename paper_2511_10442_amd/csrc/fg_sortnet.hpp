@@ -10,7 +10,7 @@ namespace fg {
 
 __host__ __device__ __forceinline__ void cmp_swap(uint64_t& lo, uint64_t& hi)
 {
-#if defined(__HIP_DEVICE_COMPILE__) && !defined(FG_CE_INT)
+#if defined(__HIP_DEVICE_COMPILE__)
     // On the device the comparator is a double-precision min / max pair: every key that reaches a network
     // (zero pins, real keys, the empty key 0x7f800001 << 32) has a sign bit of 0 and an exponent field below
     // 0x7ff, so as an IEEE double it is finite and non-negative, and finite non-negative doubles order like
@@ -35,7 +35,7 @@ __host__ __device__ __forceinline__ void cmp_swap(uint64_t& lo, uint64_t& hi)
 // smaller of two keys (same reasoning as cmp_swap)
 __host__ __device__ __forceinline__ uint64_t key_min(uint64_t x, uint64_t y)
 {
-#if defined(__HIP_DEVICE_COMPILE__) && !defined(FG_CE_INT)
+#if defined(__HIP_DEVICE_COMPILE__)
     double mn;
     asm("v_min_f64 %0, %1, %2" : "=v"(mn) : "v"(__longlong_as_double((long long)x)), "v"(__longlong_as_double((long long)y)));
     return (uint64_t)__double_as_longlong(mn);
@@ -47,7 +47,7 @@ __host__ __device__ __forceinline__ uint64_t key_min(uint64_t x, uint64_t y)
 // larger of two keys
 __host__ __device__ __forceinline__ uint64_t key_max(uint64_t x, uint64_t y)
 {
-#if defined(__HIP_DEVICE_COMPILE__) && !defined(FG_CE_INT)
+#if defined(__HIP_DEVICE_COMPILE__)
     double mx;
     asm("v_max_f64 %0, %1, %2" : "=v"(mx) : "v"(__longlong_as_double((long long)x)), "v"(__longlong_as_double((long long)y)));
     return (uint64_t)__double_as_longlong(mx);
