@@ -297,7 +297,12 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
                 useful += (e > q ? e - q : 0) + (e2 > q2 ? e2 - q2 : 0);
                 const bool second_runs = __any(e2 > q2);      // only the centre column (and shell 0) has two runs per lane
                 for (;;) {
-                    if (second_runs && q >= e && q2 < e2) { q = q2; e = e2; q2 = e2; }
+                    if (second_runs) {
+                        // a real branch on the wave-uniform flag: as selects, the switch to the second run cost four
+                        // vector instructions in every pass of every column
+                        asm volatile("");
+                        if (q >= e && q2 < e2) { q = q2; e = e2; q2 = e2; }
+                    }
                     const int32_t rem = e - q;
                     if (!__any(rem > 0)) break;
                     float w[kUnroll][NV * 4];
