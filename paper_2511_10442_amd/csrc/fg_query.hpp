@@ -1,5 +1,5 @@
 // Per-lane geometry shared by all query kernels, and the general shell-expanding walk with one
-// lane per query (any shell radius).  The walk is the cross-check path (query_algo = 1); the fast path is
+// lane per query (any shell radius).  The walk is the cross-check path (fg_query_options::algo = 1); the fast path is
 // the tile kernel plus the one-query-per-wavefront list kernel.
 //
 // What it computes (paper Section 3, Algorithm 2): for every point, the K-1 nearest other
