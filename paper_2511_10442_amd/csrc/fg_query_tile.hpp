@@ -7,10 +7,12 @@
 //   * the shell walk is wave-uniform: all 64 lanes step through the same column offsets
 //     (offsets in the first DB-1 binning dimensions) of the same shell together.  Queries of a
 //     tile are consecutive in bin order, so the bins they need for one column offset form one
-//     contiguous range of sorted points; it is staged through LDS in chunks with coalesced
-//     structure-of-arrays loads, and each lane scans only its own sub-range of the chunk (direct
-//     scan), or, in tiles whose lanes' sub-ranges differ widely, the passes of all sub-ranges are
-//     dealt out evenly over the lanes whichever query they belong to (flattened scan);
+//     contiguous range of sorted points; it is staged through LDS in chunks (the point records
+//     as the counting sort wrote them, 16-byte vectors), and each lane scans only its own
+//     sub-range of the chunk: whole bins narrowed by the box bound, then cut to the slices of
+//     the last binning dimension that the k-th best still reaches (direct scan); in tiles whose
+//     lanes' sub-ranges differ widely the passes of all sub-ranges are dealt out evenly over the
+//     lanes whichever query they belong to (flattened scan);
 //   * a candidate that beats the lane's current k-th best is appended to a small per-lane
 //     pending buffer in LDS (one write, no ordering work).  When any lane's buffer is full, and
 //     at the end of every shell, all lanes absorb their pending keys into the sorted register
@@ -22,7 +24,8 @@
 //     through LDS so that each output row is written as contiguous bytes;
 //   * the stage takes what the LDS budget of a workgroup leaves, and that budget is what lets as
 //     many workgroups share a CU as the registers allow;
-//   * lanes still uncertified when few are left are handed to the list kernel.
+//   * lanes still uncertified after shell 1 (up to five dimensions; beyond, when few are left)
+//     are handed to the list kernel.
 #pragma once
 #include "fg_query.hpp"
 #include "fg_sortnet.hpp"
