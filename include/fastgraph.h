@@ -107,9 +107,8 @@ typedef struct {
 typedef struct {
     const int32_t* dir;        /* [n] direction flags in ORIGINAL row order (see fg_binned_select_knn_dir), or NULL */
     int32_t algo;              /* 0: tile kernel + list kernel (default); 1: the one-lane-per-query shell walk for
-                                  every query (slower; kept for cross-checking); 2: the direct tile kernel with its
-                                  flattened scan on every tile instead of the uneven ones only (for tests); 3: the
-                                  direct tile kernel also for d >= 6, where 0 filters candidates on the matrix cores */
+                                  every query (slower; kept for cross-checking); 2: as 0, with the tile kernel's
+                                  flattened scan on every tile instead of the uneven ones only (for tests) */
     int32_t defer_lanes;       /* after shell 1 a wavefront of the tile kernel goes on to the next shell only while
                                   more than this many of its 64 queries are unfinished, the rest go to the list
                                   kernel; 0..64, negative: the default (64 for d <= 5, 6 beyond) */

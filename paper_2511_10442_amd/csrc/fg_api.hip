@@ -322,7 +322,7 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
     a.sub_shift = view->sub_bins == 4 ? 2 : (view->sub_bins == 2 ? 1 : 0);
     a.work_list = (int32_t*)(sc + S.work_list); a.work_count = (int32_t*)(sc + S.work_count);
     a.bin_idx = view->bin_idx; a.tile_order = (int32_t*)(sc + S.tile_order);
-    a.algo = (options && options->algo >= 1 && options->algo <= 3) ? options->algo : 0;
+    a.algo = (options && (options->algo == 1 || options->algo == 2)) ? options->algo : 0;
     a.defer_lanes = defer > 64 ? 64 : defer;
     hipError_t e = launch_query(a, d, view->d_bin, (hipStream_t)stream);
     return e == hipSuccess ? FG_OK : FG_ERR_LAUNCH;

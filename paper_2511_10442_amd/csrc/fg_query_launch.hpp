@@ -3,7 +3,6 @@
 #include "fg_query.hpp"
 #include "fg_query_tile.hpp"
 #include "fg_query_list.hpp"
-#include "fg_query_mfma.hpp"
 
 namespace fg {
 
@@ -208,23 +207,7 @@ static void launch_query_pass(const QueryArgs& a_in, hipStream_t stream)
         a.tile_order = nullptr;
     }
     const int32_t cap = a.k_list;
-    bool filtered = false;
-    if constexpr (D >= 6) {
-        // six and more coordinates: candidates filtered on the matrix cores (a.algo 2 or 3: the direct kernel)
-        if (a.algo == 0) {
-            filtered = true;
-            if (cap <= 16)
-                hipLaunchKernelGGL((k_query_tile_mfma<D, DB, 16, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), (tile_mfma_lds_bytes<16, D>()), stream, a);
-            else if (cap <= 32)
-                hipLaunchKernelGGL((k_query_tile_mfma<D, DB, 32, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), (tile_mfma_lds_bytes<32, D>()), stream, a);
-            else if (cap <= 48)
-                hipLaunchKernelGGL((k_query_tile_mfma<D, DB, 48, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), (tile_mfma_lds_bytes<48, D>()), stream, a);
-            else
-                hipLaunchKernelGGL((k_query_tile_mfma<D, DB, 64, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), (tile_mfma_lds_bytes<64, D>()), stream, a);
-        }
-    }
-    if (filtered) {
-    } else if (cap <= 16) {
+    if (cap <= 16) {
         const size_t lds = tile_sorted_lds_bytes<16, D>();
         hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 16, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     } else if (cap <= 32) {
