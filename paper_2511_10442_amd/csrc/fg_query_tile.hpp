@@ -478,6 +478,9 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
                 }
             }
         }
+        // After shell 0 a lane can only be certified with a full list: where no lane has met as many candidates as its
+        // list holds, the few pending keys wait for the first merge of shell 1 (the k-th best stays open either way).
+        if (R == 0 && !__any(active && useful >= cap)) continue;
         if constexpr (FLAT) {
             __syncthreads();
             if (__any(pend_cnt[lane] != 0)) absorb();
