@@ -70,7 +70,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 // The query stage's scratch block (fg_binning::scratch): hand-over counter first (the one word documented in the
 // header), then the work list, the tile order and an [n] array that the counting sort uses for the ranks inside
-// the bins and the query stage afterwards for the candidate permutation masked by direction flags.
+// the cells and the query stage afterwards for the tiles' hand-over marks (8 bytes per 64 points).
 struct ScratchLayout { size_t work_count, work_list, tile_order, rank, total; };
 
 ScratchLayout scratch_layout(int64_t n)
@@ -321,6 +321,7 @@ fg_status fg_query_binned(const fg_binning* view, const int32_t* row_splits, int
     a.n_bins = view->n_bins; a.cells_per_segment = (int32_t)view->cells_per_segment;
     a.sub_shift = view->sub_bins == 4 ? 2 : (view->sub_bins == 2 ? 1 : 0);
     a.work_list = (int32_t*)(sc + S.work_list); a.work_count = (int32_t*)(sc + S.work_count);
+    a.handed = (uint64_t*)(sc + S.rank);       // the counting sort is done with its ranks
     a.bin_idx = view->bin_idx; a.tile_order = (int32_t*)(sc + S.tile_order);
     a.algo = (options && (options->algo == 1 || options->algo == 2)) ? options->algo : 0;
     a.defer_lanes = defer > 64 ? 64 : defer;

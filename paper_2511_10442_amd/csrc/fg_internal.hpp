@@ -20,8 +20,9 @@ struct QueryArgs {
     int32_t* out_idx;          // [n][k]
     float* out_d2;             // [n][k]
     int32_t* out_cand;         // [n] or nullptr
-    int32_t* work_list;        // [n] sorted positions of queries deferred by the tile kernel
+    int32_t* work_list;        // [n] sorted positions of queries deferred by the tile kernel, in bin order
     int32_t* work_count;       // [1]
+    uint64_t* handed;          // [ceil(n/64)] per tile: which of its 64 queries the tile kernel hands over
     const int32_t* bin_idx;    // [n] flat bin of each point, original row order
     int32_t* tile_order;       // [2*ceil(n/64) + 128]: tile order, tile classes, class histogram, class cursors
     int32_t n;

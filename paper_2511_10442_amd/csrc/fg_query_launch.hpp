@@ -22,6 +22,37 @@ static __global__ void k_reset_query_scratch(int32_t* work_count, int32_t* tile_
     if (tile_counters && threadIdx.x < 2 * kTileClasses) tile_counters[threadIdx.x] = 0;
 }
 
+// The work list of the list kernel from the tiles' hand-over marks: blocks of 1024 tiles, the queries of a block in
+// tile order (a block's place in the list comes from one atomic add, so blocks may swap, 65 536 queries each).
+static __global__ void __launch_bounds__(1024) k_list_compact(const uint64_t* __restrict__ handed, int32_t n_tiles,
+                                                              int32_t* __restrict__ work_list, int32_t* __restrict__ work_count)
+{
+    __shared__ int32_t wave_tot[16];
+    __shared__ int32_t block_base;
+    const int32_t t = blockIdx.x * 1024 + threadIdx.x;
+    const uint64_t m = t < n_tiles ? handed[t] : 0ull;
+    const int32_t c = __popcll(m);
+    int32_t incl = c;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    for (int o = 1; o < 64; o <<= 1) {
+        const int32_t up = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += up;
+    }
+    if (lane == 63) wave_tot[wv] = incl;
+    __syncthreads();
+    int32_t before = 0, total = 0;
+    for (int j = 0; j < 16; ++j) {
+        const int32_t w = wave_tot[j];
+        if (j < wv) before += w;
+        total += w;
+    }
+    if (threadIdx.x == 0) block_base = total > 0 ? atomicAdd(work_count, total) : 0;
+    __syncthreads();
+    int32_t at = block_base + before + incl - c;
+    for (uint64_t rest = m; rest; rest &= rest - 1)
+        work_list[at++] = t * kQueryBlock + (__ffsll((unsigned long long)rest) - 1);
+}
+
 __device__ __forceinline__ int32_t tile_class(int32_t work)
 {
     if (work < 2) return work < 1 ? 0 : 1;
@@ -220,6 +251,7 @@ static void launch_query_pass(const QueryArgs& a_in, hipStream_t stream)
         const size_t lds = tile_sorted_lds_bytes<64, D>();
         hipLaunchKernelGGL((k_query_tile_sorted<D, DB, 64, COUNT, LOWER>), dim3(grid), dim3(kQueryBlock), lds, stream, a);
     }
+    hipLaunchKernelGGL(k_list_compact, dim3((grid + 1023) / 1024), dim3(1024), 0, stream, a.handed, grid, a.work_list, a.work_count);
     // one query per wavefront; four times the wave slots of the chip: the queries differ widely in cost, and with
     // more, shorter workgroups the hardware dispatcher evens them out (cursors in memory cost more than they gained)
     const int list_grid = a.n < 32768 ? a.n : 32768;

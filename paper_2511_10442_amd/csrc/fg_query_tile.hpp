@@ -507,16 +507,12 @@ __device__ __forceinline__ void tile_body(const QueryArgs& a, const int32_t tile
         }
     }
 
-    // unfinished lanes go to the work list (wave-aggregated append); their lists so far leave with the
-    // finished rows, and the first shell still to search travels in slot 0 of the distance row
+    // unfinished lanes are marked for the work list, which a small kernel then writes in tile order, i.e. bin
+    // order (appending here, in the order the tiles happen to finish, left neighbouring wavefronts of the list
+    // kernel with unrelated queries); their lists so far leave with the finished rows, and the first shell still
+    // to search travels in slot 0 of the distance row
     const uint64_t mask = __ballot(active);
-    if (mask) {
-        int32_t base = 0;
-        const int leader = __ffsll((unsigned long long)mask) - 1;
-        if (lane == leader) base = atomicAdd(a.work_count, __popcll(mask));
-        base = __shfl(base, leader, 64);
-        if (active) a.work_list[base + __popcll(mask & ((1ull << lane) - 1))] = p;
-    }
+    if (lane == 0) a.handed[tile] = mask;
     const uint32_t resume_word = (uint32_t)(R + 1);
     // Rows of exactly KC words (K = 16, 32, 48, 64) leave straight from the registers: every lane writes its own
     // row in 16-byte pieces (the pieces of a 128-byte line arrive within a few instructions of each other and are
