@@ -49,16 +49,6 @@ __device__ __forceinline__ uint64_t wave_merge64(uint64_t v, int lane)
     return v;
 }
 
-__device__ __forceinline__ int32_t wave_incl_scan_i32(int32_t v, int lane)
-{
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int32_t t = __shfl_up(v, o, 64);
-        if (lane >= o) v += t;
-    }
-    return v;
-}
-
 constexpr int kListPend = 128;
 constexpr int kListDirect = 12;   // accepted keys of one pass that are inserted one by one instead of sorted
 
@@ -140,10 +130,16 @@ k_query_list_wave(QueryArgs a)
                 {
                     int32_t o[DB - 1];
                     int32_t rem = ok ? t : 0;
+                    // digits of the column number in base `side`; up to 2^16 columns the quotient comes from a float
+                    // reciprocal (the true quotient of rem + 1/2 lies at least 1/(2 side) from an integer, the
+                    // product errs by less than a hundredth: exact), which saves two integer divisions per lane
+                    const bool small = ncols <= 65536;
+                    const float inv_side = 1.0f / (float)side;
 #pragma unroll
                     for (int c = DB - 2; c >= 0; --c) {
-                        const int32_t v = rem % side;
-                        rem /= side;
+                        const int32_t quo = small ? (int32_t)(((float)rem + 0.5f) * inv_side) : rem / side;
+                        const int32_t v = rem - quo * side;
+                        rem = quo;
                         o[c] = (v & 1) ? ((v + 1) >> 1) : -(v >> 1);
                         surf = surf || o[c] == R || o[c] == -R;
                     }
@@ -196,8 +192,8 @@ k_query_list_wave(QueryArgs a)
                     }
                 }
                 const int32_t len1 = b1 - a1, len = len1 + (b2 - a2);
-                const int32_t incl = wave_incl_scan_i32(len, lane);
-                const int32_t W = __shfl(incl, kQueryBlock - 1, 64);
+                const int32_t incl = wave_incl_scan_dpp_i32(len);
+                const int32_t W = __builtin_amdgcn_readlane(incl, kQueryBlock - 1);
                 __syncthreads();
                 seg_excl[lane] = incl - len; seg_a1[lane] = a1; seg_len1[lane] = len1; seg_a2[lane] = a2;
                 __syncthreads();
